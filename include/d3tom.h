@@ -1,0 +1,195 @@
+/*
+ * d3tom.h — C ABI of the MI355X (gfx950) library for the D3ToM merge layer and the
+ * bidirectional attention over the shortened sequence that follows it.
+ *
+ * One denoising step of the method, at the merge layer (Algorithm 1, the block guarded by
+ * "l = l* and the decider set is not empty"):
+ *
+ *     d3tom_importance   S_j = sum over decider rows of the attention they pay to visual token j
+ *     d3tom_select_topk  keep the ceil(keep_ratio |V|) highest-scoring visual tokens
+ *     d3tom_merge        send every other visual token to its most cosine-similar kept token,
+ *                        aggregate, and physically remove the merged positions
+ *     d3tom_attend       full (unmasked) attention over the shortened sequence
+ *
+ * Conventions shared by the four device entry points
+ * --------------------------------------------------
+ * Pointers   Every pointer is a DEVICE pointer owned by the caller, unless the parameter is
+ *            documented "host".  The library never allocates, frees or keeps a pointer.
+ * Batching   B samples are concatenated along the token axis.  Per-sample metadata are device
+ *            int32 arrays; everything the host needs to size a launch is passed by value
+ *            (B, H, dh, max_*).  Values in device metadata that exceed the stated maxima are
+ *            clamped by the kernels (no out-of-bounds access); results for such samples are
+ *            unspecified.
+ * Layout     Token-major rows.  q/k/v: [tokens, H, dh], heads contiguous inside a row.
+ *            Hidden states: [tokens, d].  Rows must be 16-byte aligned (dh and d multiples of
+ *            8 for bf16, of 4 for f32; base pointers 16-byte aligned).
+ * Types      D3TOM_F32: IEEE float.  D3TOM_BF16: bfloat16 storage, float32 accumulation.
+ * Stream     All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *            default stream).  No entry point synchronises or reads device memory on the host.
+ * Workspace  `ws` is device scratch of at least d3tom_workspace_bytes(op, ...) bytes, 256-byte
+ *            aligned.  It carries no state between calls; concurrent calls need separate ones.
+ * Errors     The return value is a d3tom_status.  Arguments are validated on the host before
+ *            anything is enqueued; on any status other than D3TOM_OK nothing was enqueued.
+ * Determinism  No floating-point atomics: the same inputs give bit-identical outputs.
+ * NaN/Inf inputs are outside the contract.
+ */
+#ifndef D3TOM_H
+#define D3TOM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    D3TOM_OK = 0,
+    D3TOM_ERR_INVALID_ARG = 1,        /* null pointer, non-positive size, misaligned pointer        */
+    D3TOM_ERR_NO_DECIDERS = 2,        /* a sample has an empty decider set: skip the merge          */
+    D3TOM_ERR_WORKSPACE_TOO_SMALL = 3,
+    D3TOM_ERR_UNSUPPORTED = 4,        /* shape or type outside what the kernels are built for       */
+    D3TOM_ERR_DEVICE = 5              /* the HIP runtime rejected a launch                          */
+} d3tom_status;
+
+typedef enum { D3TOM_F32 = 0, D3TOM_BF16 = 1 } d3tom_dtype;
+typedef enum { D3TOM_MERGE_MEAN = 0, D3TOM_MERGE_SUM = 1 } d3tom_merge_mode;
+typedef enum { D3TOM_OP_IMPORTANCE = 0, D3TOM_OP_SELECT_TOPK = 1, D3TOM_OP_MERGE = 2, D3TOM_OP_ATTEND = 3 } d3tom_op;
+
+/* Largest visual-token count per sample that select_topk / merge keep resident in LDS. */
+#define D3TOM_MAX_VISUAL 16384
+/* Largest decider count per sample. */
+#define D3TOM_MAX_DECIDERS 256
+
+/* ------------------------------------------------------------------------------------------
+ * Host-only helpers (no device work).
+ * ---------------------------------------------------------------------------------------- */
+
+/* Number of visual tokens kept at a keep ratio (= 1 - merge ratio alpha_t).  Section 3.2 keeps
+ * the tokens whose score rank is at most (1 - alpha_t)|V|; a fractional product is rounded up:
+ * ceil(keep_ratio * V - 1e-9), clamped to [1, V].  Returns 0 if V < 1. */
+int d3tom_keep_count(int V, double keep_ratio);
+
+/* Linear timestep-dependent schedule (Section 3.2, "Timestep-Dependent Merge Schedule"): the
+ * value at decoding-order step `step` in 0..T-1, moving linearly from r_first to r_last.  The
+ * caller decides whether the quantity is a merge ratio or a keep ratio and which way it runs. */
+double d3tom_schedule(int step, int T, double r_first, double r_last);
+
+/* Theoretical FLOPs of a whole denoising trajectory under the paper's cost model (Section 4.3
+ * and Appendix B): FLOPs_layer(n) = 4 n d^2 + 2 n^2 d + 3 n d m; the merge inside layer l_star
+ * at constant merge ratio alpha adds 2 alpha (1-alpha) |V|^2 d + alpha |V| d per step; the first
+ * of the T steps runs unmerged (empty decider set).  alpha = 0 gives the unmerged baseline. */
+double d3tom_model_flops(double alpha, int l_star, int L, int T, int V, int P, int O, int d, int m);
+
+/* Bytes of workspace the given entry point needs for at most B samples of at most max_N tokens,
+ * max_V visual tokens and max_D deciders each, with H heads of size dh (d = H * dh). */
+size_t d3tom_workspace_bytes(int op, int B, int max_N, int max_V, int H, int dh, int max_D);
+
+/* Static, human-readable name of a status code. */
+const char* d3tom_status_string(int status);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_importance — decider-guided importance map (Section 3.2, "The Decider-Guided
+ * Mechanism": attention matrix A and S_j = sum_{i in D} A_ij; Algorithm 1, the line forming S).
+ *
+ * For sample b, head h and decider row i: softmax over ALL keys of the sample of
+ * scale * q[i,h,:] . k[j,h,:]; the probabilities are summed over the sample's decider rows and
+ * averaged over heads; only the visual columns are written.  The N x N matrix is never formed.
+ *
+ *   q, k        [seq_off[B], H, dh]  dt
+ *   seq_off     int32[B+1]  first token of each sample (seq_off[0] = 0)
+ *   dec_idx     int32[dec_off[B]]  decider positions, relative to the sample's first token
+ *   dec_off     int32[B+1]
+ *   min_D,max_D host-known smallest / largest decider count over the batch
+ *   vis_start   int32[B]  first visual token, relative to the sample's first token
+ *   vis_count   int32[B]  |V| of each sample
+ *   score_off   int32[B+1]  offsets into `scores` (prefix sums of vis_count)
+ *   max_N,max_V host-known largest token / visual-token count per sample
+ *   scores      float[score_off[B]]  out
+ *
+ * min_D == 0 returns D3TOM_ERR_NO_DECIDERS (Algorithm 1 skips the merge when the decider set is
+ * empty; the caller then runs the layer at full length).  max_D > D3TOM_MAX_DECIDERS or a dh the
+ * kernels are not built for (bf16: 64 or 128; f32: any multiple of 4 up to 256) returns
+ * D3TOM_ERR_UNSUPPORTED.
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_importance(const void* q, const void* k, int dt,
+                     int B, const int32_t* seq_off, int H, int dh, float scale,
+                     const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                     const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                     int max_N, int max_V,
+                     float* scores, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_select_topk — keep / merge partition (Section 3.2: V_kept holds the tokens whose rank is
+ * at most the kept count; Algorithm 1, the TopK line).
+ *
+ * Rank order is (score descending, index ascending): equal scores at the threshold go to the
+ * lower index.  Output order is ascending position (positions are removed, never reordered).
+ *
+ *   scores    float[score_off[B]]
+ *   keep_k    int32[B]   kept count per sample, 1 <= keep_k[b] <= vis_count[b] (d3tom_keep_count)
+ *   kept_off  int32[B+1] offsets into kept_idx (prefix sums of keep_k)
+ *   max_V     host-known largest |V|; above D3TOM_MAX_VISUAL returns D3TOM_ERR_UNSUPPORTED
+ *   kept_idx  int32[kept_off[B]]  out: kept tokens, ascending, relative to the visual block
+ *   slot_of   int32[score_off[B]] out: kept token -> its index in kept_idx (0..k-1), other -> -1
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_select_topk(const float* scores, int B, const int32_t* score_off, const int32_t* keep_k,
+                      const int32_t* kept_off, int max_V,
+                      int32_t* kept_idx, int32_t* slot_of,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_merge — similarity-based merging (Section 3.2, "Similarity-Based Merging": cosine argmax
+ * over the kept set, h_k* <- h_k* + h_m, removal of the merged positions; Algorithm 1, the FORALL
+ * block and the "Remove positions" line; Section 4.4 for similarity taken on other features).
+ *
+ * Every pruned visual token m goes to slot argmax_r cos(sim_m, sim_kept[r]), computed from the
+ * rows as given (all assignments first, aggregation afterwards); ties go to the lowest slot; a
+ * zero row has cosine 0 with everything.  Output rows of sample b:
+ *     [rows before the visual block | keep_k merged rows, ascending position | rows after it]
+ * MEAN: merged row = (sum of member rows) / member count.  SUM: the plain sum (the paper's literal
+ * update).  Accumulation is float32 in ascending member order, rounded once on store; a slot with
+ * no absorbed token, and every non-visual row, is copied bit-exactly.
+ *
+ *   x         [seq_off[B], d]  dt   payload rows
+ *   sim       NULL (use x) or [seq_off[B], d_sim] dt: rows the cosine is taken on
+ *   d, d_sim  row lengths (d_sim ignored when sim is NULL)
+ *   kept_idx, kept_off   as written by d3tom_select_topk
+ *   max_N, max_V, max_keep  host-known maxima over the batch
+ *   out_off   int32[B+1]  first output row of each sample; sample b emits
+ *             N_b - (vis_count[b] - keep_k[b]) rows (Section 3.2, the post-merge length)
+ *   y         [out_off[B], d] dt  out
+ *   assign    int32[score_off-like: sum V_b] out or NULL: slot of every visual token
+ *   counts    int32[kept_off[B]]  out or NULL: members per slot, the kept token included
+ *   src_pos   int32[out_off[B]]   out or NULL: original position (within the sample) of each row
+ *   vis_off   int32[B+1]  offsets of each sample's visual block into `assign` (prefix sums of
+ *             vis_count)
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
+                int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
+                const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
+                int max_N, int max_V, int max_keep, int mode,
+                const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
+                void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_attend — bidirectional attention over the shortened sequence (Section 3.2: the shortened
+ * tensor propagates through the later layers; Section 4.3: the 2 n^2 d term of FLOPs_layer; the
+ * model attends without a causal mask).
+ *
+ * Per sample and head: o = softmax(scale * q k^T) v over all keys of the sample (variable-length
+ * batch, no mask, no dropout).  bf16: MFMA with float32 online-softmax state; f32: plain float.
+ *
+ *   q, k, v     [cu_seqlens[B], H, dh] dt
+ *   cu_seqlens  int32[B+1]  first token of each sample
+ *   max_seqlen  host-known longest sample
+ *   o           [cu_seqlens[B], H, dh] dt  out
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_attend(const void* q, const void* k, const void* v, int dt,
+                 int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
+                 void* o, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* D3TOM_H */

@@ -49,13 +49,13 @@ def lib():
                                         _i32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _f64p, _f64p]
         L.oracle_select_topk.argtypes = [_f64p, ctypes.c_int, ctypes.c_int, _i32p, _i32p]
         L.oracle_assign.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p, ctypes.c_int,
-                                    _i32p, _f64p]
+                                    _i32p, _f64p, _i32p]
         L.oracle_cosine.restype = ctypes.c_double
         L.oracle_cosine.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
         L.oracle_merge.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p,
                                    ctypes.c_int, _i32p, ctypes.c_int, _f64p, _i32p, _i32p]
         L.oracle_attend.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                    ctypes.c_double, _f64p]
+                                    ctypes.c_double, _f64p, _i32p, ctypes.c_int]
         for name, n in (("oracle_flops_layer", 3), ("oracle_flops_attn", 2), ("oracle_flops_ffn", 3),
                         ("oracle_flops_merge", 3)):
             f = getattr(L, name)
@@ -123,14 +123,20 @@ def select_topk(S, keep_k: int) -> Tuple[np.ndarray, np.ndarray]:
     return kept, slot
 
 
-def assign(f, vis_start: int, V: int, kept_idx, return_cos: bool = False):
-    """assign[V]: slot of every visual token (cosine argmax for pruned ones)."""
+def assign(f, vis_start: int, V: int, kept_idx, return_cos: bool = False, only=None):
+    """assign[V]: slot of every visual token (cosine argmax for pruned ones).
+
+    `only`: optional list of visual indices; pruned tokens outside it are skipped (assign = -1)."""
     f = _f32(f); kept = _i32(kept_idx)
     d = f.shape[1]
     a = np.zeros(V, dtype=np.int32)
     bc = np.zeros(V, dtype=np.float64)
+    mask = None
+    if only is not None:
+        mask = np.zeros(V, dtype=np.int32)
+        mask[np.asarray(only, dtype=np.int64)] = 1
     _check(lib().oracle_assign(_p(f, _f32p), d, int(vis_start), int(V), _p(kept, _i32p), len(kept),
-                               _p(a, _i32p), _p(bc, _f64p)), "assign")
+                               _p(a, _i32p), _p(bc, _f64p), _p(mask, _i32p) if mask is not None else None), "assign")
     return (a, bc) if return_cos else a
 
 
@@ -154,15 +160,16 @@ def merge(x, vis_start: int, V: int, kept_idx, assign_, mode: str = "mean"):
     return y, counts, src
 
 
-def attend(q, k, v, scale: Optional[float] = None) -> np.ndarray:
-    """out [n, H, dh] float64, no mask."""
+def attend(q, k, v, scale: Optional[float] = None, rows=None) -> np.ndarray:
+    """out [n, H, dh] float64, no mask.  `rows`: optional query rows to evaluate (others stay 0)."""
     q = _f32(q); k = _f32(k); v = _f32(v)
     n, H, dh = q.shape
     assert k.shape == q.shape and v.shape == q.shape
     scale = 1.0 / np.sqrt(dh) if scale is None else scale
     out = np.zeros((n, H, dh), dtype=np.float64)
-    _check(lib().oracle_attend(_p(q, _f32p), _p(k, _f32p), _p(v, _f32p), n, H, dh, float(scale), _p(out, _f64p)),
-           "attend")
+    r = _i32(rows) if rows is not None else None
+    _check(lib().oracle_attend(_p(q, _f32p), _p(k, _f32p), _p(v, _f32p), n, H, dh, float(scale), _p(out, _f64p),
+                               _p(r, _i32p) if r is not None else None, len(r) if r is not None else 0), "attend")
     return out
 
 

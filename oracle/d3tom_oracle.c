@@ -143,9 +143,12 @@ int oracle_select_topk(const double* S, int V, int keep_k, int32_t* kept_idx, in
  *   kept_idx [keep_k]     ascending indices inside the visual block
  *   assign   [V]  out     slot every visual token ends up in (kept token: its own slot)
  *   best_cos [V]  out, optional: similarity to the chosen slot (1 for kept tokens)
+ *   only     [V]  optional mask: when given, pruned tokens with only[m] == 0 are skipped and get
+ *                 assign[m] = -1 (lets a test look at a sample of rows of a large case)
  */
 int oracle_assign(const float* f, int d, int vis_start, int V,
-                  const int32_t* kept_idx, int keep_k, int32_t* assign, double* best_cos) {
+                  const int32_t* kept_idx, int keep_k, int32_t* assign, double* best_cos,
+                  const int32_t* only) {
     if (d <= 0 || V <= 0 || keep_k < 1 || keep_k > V) return 1;
     double* nrm = (double*)malloc((size_t)V * sizeof(double));
     int32_t* slot_of = (int32_t*)malloc((size_t)V * sizeof(int32_t));
@@ -164,6 +167,7 @@ int oracle_assign(const float* f, int d, int vis_start, int V,
 #pragma omp parallel for schedule(dynamic, 8)
     for (int m = 0; m < V; ++m) {
         if (slot_of[m] >= 0) { assign[m] = slot_of[m]; if (best_cos) best_cos[m] = 1.0; continue; }
+        if (only && !only[m]) { assign[m] = -1; if (best_cos) best_cos[m] = 0.0; continue; }
         const float* xm = f + (size_t)(vis_start + m) * d;
         int best = -1; double bc = 0.0;
         for (int r = 0; r < keep_k; ++r) {
@@ -245,13 +249,17 @@ int oracle_merge(const float* x, int N, int d, int vis_start, int V,
  * key).  Per head: O = softmax(scale * Q K^T) V.
  *
  *   q, k, v [n, H, dh]   out [n, H, dh]
+ *   rows    [n_rows] optional: query rows to evaluate (NULL = all n); other rows of out are left alone
  */
 int oracle_attend(const float* q, const float* k, const float* v, int n, int H, int dh, double scale,
-                  double* out) {
+                  double* out, const int32_t* rows, int n_rows) {
     if (n <= 0 || H <= 0 || dh <= 0) return 1;
+    if (!rows) n_rows = n;
+    for (int t = 0; rows && t < n_rows; ++t) if (rows[t] < 0 || rows[t] >= n) return 1;
 #pragma omp parallel for collapse(2) schedule(dynamic, 16)
     for (int h = 0; h < H; ++h) {
-        for (int i = 0; i < n; ++i) {
+        for (int t = 0; t < n_rows; ++t) {
+            const int i = rows ? rows[t] : t;
             double* p = (double*)malloc((size_t)n * sizeof(double));
             const float* qi = q + ((size_t)i * H + h) * dh;
             double mx = -INFINITY;

@@ -1,0 +1,369 @@
+// d3tom_importance: decider-guided importance map (Section 3.2, "The Decider-Guided Mechanism";
+// Algorithm 1, the line that forms S).
+//
+// S_j = (1/H) sum_h sum_{i in D} softmax_j(scale * q_{i,h} . k_{j,h}), softmax over ALL keys of the
+// sample, written for the visual columns only.  The N x N matrix is never formed: only the |D|
+// decider rows are ever evaluated, in two sweeps over K:
+//
+//   sweep 1 (stats)   per (head, decider): running max and sum of exp2 over all keys, computed per
+//                     128-key chunk by one workgroup each and combined later in a fixed order
+//   sweep 2 (scores)  per (head, visual key): sum over deciders of exp2(logit - logsumexp); the
+//                     per-head partial rows are added in head order by whichever workgroup of a key
+//                     chunk finishes last (integer arrival counter, no float atomics)
+//
+// bf16 path: logits on MFMA 16x16x32 (rows = 16 deciders, cols = 16 keys, contraction = dh), both
+// operands read straight from HBM/L2 in the MFMA operand layout (each lane reads dh/4 contiguous
+// elements of its row; the contraction index is permuted identically for both operands, which a
+// dot product does not see).  Everything is bandwidth bound: K is streamed twice, the second time
+// usually from the memory-side cache.
+//
+// The generic path (any float type / head size) is a plain one-thread-per-output kernel pair.
+#include "common.hpp"
+
+namespace d3tom {
+
+constexpr int IMP_KC = 128;                    // keys per workgroup (4 waves x SUB sub-tiles x 16)
+constexpr int IMP_SUB = IMP_KC / (4 * 16);
+
+struct ImpWs {
+    size_t part_off, sp_off, cnt_off, c_off, total;
+    int NCH, NCHV, DPAD, VPAD;
+};
+__host__ inline ImpWs imp_ws_layout(int B, int max_N, int max_V, int H, int max_D) {
+    ImpWs w;
+    w.NCH = ceil_div(max_N, IMP_KC);
+    w.NCHV = ceil_div(max_V, IMP_KC);
+    w.DPAD = ceil_div(max_D, 16) * 16;
+    w.VPAD = w.NCHV * IMP_KC;
+    size_t o = 0;
+    w.part_off = o; o += align_up((size_t)B * H * w.NCH * w.DPAD * sizeof(float2), 256);
+    w.sp_off = o;   o += align_up((size_t)B * H * w.VPAD * sizeof(float), 256);
+    w.cnt_off = o;  o += align_up((size_t)B * w.NCHV * sizeof(int), 256);
+    w.c_off = o;    o += align_up((size_t)B * H * max_D * sizeof(float), 256);   // generic path
+    w.total = o;
+    return w;
+}
+size_t importance_ws_bytes(int B, int max_N, int max_V, int H, int dh, int max_D) {
+    (void)dh;
+    return imp_ws_layout(B, max_N, max_V, H, max_D).total;
+}
+
+// Load one MFMA operand row fragment: lane (r = lane % 16, g = lane / 16) takes elements
+// [g*DH/4 + kk*8, +8) of its row for k-step kk.
+template <int DH>
+__device__ __forceinline__ void load_frag(const uint16_t* row, int g, bool valid, bf16x8 (&f)[DH / 32]) {
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(row + g * (DH / 4));
+#pragma unroll
+    for (int kk = 0; kk < DH / 32; ++kk) {
+        bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+        f[kk] = valid ? p[kk] : z;
+    }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void imp_stats_bf16(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
+    int max_D, int DPAD, int NCH, float2* __restrict__ part, int* __restrict__ counters, int NCHV) {
+    constexpr int KS = DH / 32;
+    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tok0 = seq_off[b];
+    const int N = seq_off[b + 1] - tok0;
+    const int D = min(dec_off[b + 1] - dec_off[b], max_D);
+    const int32_t* dec = dec_idx + dec_off[b];
+    if (chunk == 0 && h == 0)
+        for (int t = threadIdx.x; t < NCHV; t += 256) counters[b * NCHV + t] = 0;
+    const int key_base = chunk * IMP_KC;
+    if (key_base >= N || D <= 0) return;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    __shared__ float2 wstat[4][D3TOM_MAX_DECIDERS];
+
+    bf16x8 kf[IMP_SUB][KS];
+    bool kvalid[IMP_SUB];
+#pragma unroll
+    for (int s = 0; s < IMP_SUB; ++s) {
+        const int key = key_base + (wave * IMP_SUB + s) * 16 + r;
+        kvalid[s] = key < N;
+        const uint16_t* row = k + ((size_t)(tok0 + (kvalid[s] ? key : 0)) * H + h) * DH;
+        load_frag<DH>(row, g, kvalid[s], kf[s]);
+    }
+    const int nblk = (D + 15) >> 4;
+    for (int db = 0; db < nblk; ++db) {
+        const int i = db * 16 + r;
+        const bool qv = i < D;
+        int pos = qv ? dec[i] : 0;
+        pos = min(max(pos, 0), N - 1);
+        bf16x8 qf[KS];
+        load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf);
+        float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+        float z[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < IMP_SUB; ++s) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[kk], kf[s][kk], acc, 0, 0, 0);
+            // acc[e]: decider row db*16 + 4g + e, key column r of sub-tile s
+            if (kvalid[s]) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float l2 = acc[e] * scale2;
+                    const float mn = fmaxf(m[e], l2);
+                    z[e] = z[e] * exp2f(m[e] - mn) + exp2f(l2 - mn);
+                    m[e] = mn;
+                }
+            }
+        }
+        // combine over the 16 key columns (lanes with equal g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) {
+                const float m2 = __shfl_xor(m[e], o, WAVE);
+                const float z2 = __shfl_xor(z[e], o, WAVE);
+                lse2_combine(m[e], z[e], m2, z2);
+            }
+            if (r == 0) wstat[wave][db * 16 + 4 * g + e] = make_float2(m[e], z[e]);
+        }
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < nblk * 16; t += 256) {
+        float2 a = wstat[0][t];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) lse2_combine(a.x, a.y, wstat[w][t].x, wstat[w][t].y);
+        part[((size_t)(b * H + h) * NCH + chunk) * DPAD + t] = a;
+    }
+}
+
+template <int DH>
+__global__ __launch_bounds__(256) void imp_scores_bf16(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
+    const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count, const int32_t* __restrict__ score_off,
+    int max_D, int max_V, int DPAD, int NCH, int NCHV, int VPAD,
+    const float2* __restrict__ part, float* __restrict__ sp, int* __restrict__ counters, float* __restrict__ scores) {
+    constexpr int KS = DH / 32;
+    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tok0 = seq_off[b];
+    const int N = seq_off[b + 1] - tok0;
+    const int D = min(dec_off[b + 1] - dec_off[b], max_D);
+    const int32_t* dec = dec_idx + dec_off[b];
+    int vs = min(max(vis_start[b], 0), N);
+    const int V = min(min(vis_count[b], max_V), N - vs);
+    const int key_base = chunk * IMP_KC;
+    if (key_base >= V || D <= 0) return;
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
+    __shared__ float c_lds[D3TOM_MAX_DECIDERS];
+    __shared__ int s_last;
+
+    // log2-sum-exp2 of every decider row of this head, chunks combined in ascending order
+    const int nch = (N + IMP_KC - 1) / IMP_KC;
+    for (int t = threadIdx.x; t < D; t += 256) {
+        const float2* p = part + ((size_t)(b * H + h) * NCH) * DPAD + t;
+        float m = -INFINITY, z = 0.f;
+        for (int c = 0; c < nch; ++c) {
+            const float2 a = p[(size_t)c * DPAD];
+            lse2_combine(m, z, a.x, a.y);
+        }
+        c_lds[t] = m + log2f(z);
+    }
+    __syncthreads();
+
+    bf16x8 kf[IMP_SUB][KS];
+    float acc_s[IMP_SUB];
+#pragma unroll
+    for (int s = 0; s < IMP_SUB; ++s) {
+        const int j = key_base + (wave * IMP_SUB + s) * 16 + r;
+        const bool kv = j < V;
+        const uint16_t* row = k + ((size_t)(tok0 + vs + (kv ? j : 0)) * H + h) * DH;
+        load_frag<DH>(row, g, kv, kf[s]);
+        acc_s[s] = 0.f;
+    }
+    const int nblk = (D + 15) >> 4;
+    for (int db = 0; db < nblk; ++db) {
+        const int i = db * 16 + r;
+        const bool qv = i < D;
+        int pos = qv ? dec[i] : 0;
+        pos = min(max(pos, 0), N - 1);
+        bf16x8 qf[KS];
+        load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf);
+        float cc[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int row = db * 16 + 4 * g + e;
+            cc[e] = (row < D) ? c_lds[row] : INFINITY;          // padded rows contribute exp2(-inf) = 0
+        }
+#pragma unroll
+        for (int s = 0; s < IMP_SUB; ++s) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[kk], kf[s][kk], acc, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc_s[s] += exp2f(acc[e] * scale2 - cc[e]);
+        }
+    }
+    float* sp_row = sp + (size_t)(b * H + h) * VPAD;
+#pragma unroll
+    for (int s = 0; s < IMP_SUB; ++s) {
+        float v = acc_s[s];
+        v += __shfl_xor(v, 16, WAVE);
+        v += __shfl_xor(v, 32, WAVE);
+        if (g == 0) sp_row[key_base + (wave * IMP_SUB + s) * 16 + r] = v;
+    }
+    // arrival counter: the last head to finish this key chunk adds the H partial rows in head order
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) s_last = (atomicAdd(&counters[b * NCHV + chunk], 1) == H - 1);
+    __syncthreads();
+    if (!s_last) return;
+    __threadfence();
+    const float invH = 1.0f / (float)H;
+    for (int t = threadIdx.x; t < IMP_KC; t += 256) {
+        const int j = key_base + t;
+        if (j < V) {
+            float s = 0.f;
+            for (int hh = 0; hh < H; ++hh)
+                s += __builtin_nontemporal_load(sp + (size_t)(b * H + hh) * VPAD + j);
+            scores[score_off[b] + j] = s * invH;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// generic path: one workgroup per (decider, head) for the stats, one thread per visual key for
+// the scores.  Plain float arithmetic, any head size up to 256.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void imp_stats_generic(
+    const T* __restrict__ q, const T* __restrict__ k, int H, int dh, float scale2,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
+    int max_D, float* __restrict__ cws) {
+    const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tok0 = seq_off[b];
+    const int N = seq_off[b + 1] - tok0;
+    const int D = min(dec_off[b + 1] - dec_off[b], max_D);
+    if (i >= D) return;
+    __shared__ float qs[256];
+    __shared__ float2 red[4];
+    const int pos = min(max(dec_idx[dec_off[b] + i], 0), N - 1);
+    for (int c = threadIdx.x; c < dh; c += 256) qs[c] = Elem<T>::load(q + ((size_t)(tok0 + pos) * H + h) * dh + c);
+    __syncthreads();
+    float m = -INFINITY, z = 0.f;
+    for (int j = threadIdx.x; j < N; j += 256) {
+        const T* kr = k + ((size_t)(tok0 + j) * H + h) * dh;
+        float s = 0.f;
+        for (int c = 0; c < dh; ++c) s += qs[c] * Elem<T>::load(kr + c);
+        lse2_combine(m, z, s * scale2, 1.0f);
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const float m2 = __shfl_xor(m, o, WAVE), z2 = __shfl_xor(z, o, WAVE);
+        lse2_combine(m, z, m2, z2);
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = make_float2(m, z);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float2 a = red[0];
+        for (int w = 1; w < 4; ++w) lse2_combine(a.x, a.y, red[w].x, red[w].y);
+        cws[(size_t)(b * H + h) * max_D + i] = a.x + log2f(a.y);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void imp_scores_generic(
+    const T* __restrict__ q, const T* __restrict__ k, int H, int dh, float scale2,
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
+    const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count, const int32_t* __restrict__ score_off,
+    int max_D, int max_V, const float* __restrict__ cws, float* __restrict__ scores) {
+    const int b = blockIdx.y;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    const int tok0 = seq_off[b];
+    const int N = seq_off[b + 1] - tok0;
+    const int D = min(dec_off[b + 1] - dec_off[b], max_D);
+    const int vs = min(max(vis_start[b], 0), N);
+    const int V = min(min(vis_count[b], max_V), N - vs);
+    if (j >= V || D <= 0) return;
+    float acc = 0.f;
+    for (int h = 0; h < H; ++h) {
+        const T* kr = k + ((size_t)(tok0 + vs + j) * H + h) * dh;
+        for (int i = 0; i < D; ++i) {
+            const int pos = min(max(dec_idx[dec_off[b] + i], 0), N - 1);
+            const T* qr = q + ((size_t)(tok0 + pos) * H + h) * dh;
+            float s = 0.f;
+            for (int c = 0; c < dh; ++c) s += Elem<T>::load(qr + c) * Elem<T>::load(kr + c);
+            acc += exp2f(s * scale2 - cws[(size_t)(b * H + h) * max_D + i]);
+        }
+    }
+    scores[score_off[b] + j] = acc / (float)H;
+}
+
+}  // namespace d3tom
+
+using namespace d3tom;
+
+extern "C" int d3tom_importance(const void* q, const void* k, int dt,
+                                int B, const int32_t* seq_off, int H, int dh, float scale,
+                                const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                                const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                                int max_N, int max_V,
+                                float* scores, void* ws, size_t ws_bytes, void* stream) {
+    if (!q || !k || !seq_off || !dec_idx || !dec_off || !vis_start || !vis_count || !score_off || !scores)
+        return D3TOM_ERR_INVALID_ARG;
+    if (B < 1 || H < 1 || dh < 1 || max_N < 1 || max_V < 1 || max_V > max_N || min_D < 0 || max_D < min_D)
+        return D3TOM_ERR_INVALID_ARG;
+    if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k)) return D3TOM_ERR_INVALID_ARG;
+    if (min_D == 0) return D3TOM_ERR_NO_DECIDERS;
+    if (max_D > D3TOM_MAX_DECIDERS) return D3TOM_ERR_UNSUPPORTED;
+    if (dh > 256 || (dt == D3TOM_BF16 ? (dh % 8) : (dh % 4))) return D3TOM_ERR_UNSUPPORTED;
+    const ImpWs w = imp_ws_layout(B, max_N, max_V, H, max_D);
+    if (!ws || ws_bytes < w.total || (((uintptr_t)ws) & 255u)) return ws ? D3TOM_ERR_WORKSPACE_TOO_SMALL : D3TOM_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    char* wsb = (char*)ws;
+    const float scale2 = scale * LOG2E;
+
+    if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
+        float2* part = (float2*)(wsb + w.part_off);
+        float* sp = (float*)(wsb + w.sp_off);
+        int* cnt = (int*)(wsb + w.cnt_off);
+        const dim3 g1(w.NCH, H, B), g2(w.NCHV, H, B);
+        if (dh == 128) {
+            imp_stats_bf16<128><<<g1, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
+                                                    dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV);
+            D3TOM_LAUNCH_CHECK();
+            imp_scores_bf16<128><<<g2, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
+                                                     dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
+                                                     w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores);
+        } else {
+            imp_stats_bf16<64><<<g1, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
+                                                   dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV);
+            D3TOM_LAUNCH_CHECK();
+            imp_scores_bf16<64><<<g2, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
+                                                    dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
+                                                    w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores);
+        }
+        D3TOM_LAUNCH_CHECK();
+        return D3TOM_OK;
+    }
+    float* cws = (float*)(wsb + w.c_off);
+    const dim3 g1(max_D, H, B), g2(ceil_div(max_V, 256), B);
+    if (dt == D3TOM_F32) {
+        imp_stats_generic<float><<<g1, 256, 0, st>>>((const float*)q, (const float*)k, H, dh, scale2, seq_off, dec_idx,
+                                                     dec_off, max_D, cws);
+        D3TOM_LAUNCH_CHECK();
+        imp_scores_generic<float><<<g2, 256, 0, st>>>((const float*)q, (const float*)k, H, dh, scale2, seq_off, dec_idx,
+                                                      dec_off, vis_start, vis_count, score_off, max_D, max_V, cws, scores);
+    } else {
+        imp_stats_generic<uint16_t><<<g1, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, dh, scale2, seq_off,
+                                                        dec_idx, dec_off, max_D, cws);
+        D3TOM_LAUNCH_CHECK();
+        imp_scores_generic<uint16_t><<<g2, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, dh, scale2, seq_off,
+                                                         dec_idx, dec_off, vis_start, vis_count, score_off, max_D, max_V,
+                                                         cws, scores);
+    }
+    D3TOM_LAUNCH_CHECK();
+    return D3TOM_OK;
+}

@@ -1,0 +1,567 @@
+// d3tom_merge: similarity-based merging (Section 3.2, "Similarity-Based Merging"; Algorithm 1, the
+// FORALL block and the "Remove positions" line).
+//
+// Stages, all on the caller's stream:
+//   prep      complement of kept_idx -> ascending list of pruned visual tokens          (1 WG / sample)
+//   norms     1 / ||row|| of every visual row of the similarity features               (1 wave / row)
+//   cosine    pruned x kept similarity GEMM on MFMA 32x32x16 bf16 with the argmax fused into the
+//             epilogue: only (best value, best slot) per (pruned row, 128-slot column tile) ever
+//             leaves the registers; the M x k matrix is never written
+//   finalize  argmax across column tiles (ascending, strict '>' : ties go to the lowest slot), then a
+//             counting sort of all visual tokens by destination slot into a CSR (segment offsets +
+//             member list, members ascending inside each segment)                       (1 WG / sample)
+//   scatter   one workgroup per OUTPUT row: merged rows stream their members with 16-byte loads and
+//             accumulate in float32 in ascending member order, other rows are copied; one store per
+//             element, no atomics, so the result is bit-reproducible
+//
+// All similarities are taken on the rows as given (assignment first, aggregation afterwards).
+#include "common.hpp"
+
+namespace d3tom {
+
+constexpr int COS_BN = 128;        // kept slots per column tile
+constexpr int COS_BK = 64;         // contraction elements per LDS stage
+constexpr int COS_LDA = COS_BK + 8;   // padded LDS row length (elements)
+constexpr int FIN_THREADS = 1024;
+
+struct MergeWs {
+    size_t pruned_off, rnorm_off, part_off, assign_off, seg_off, mem_off, total;
+    int NCT;
+};
+__host__ inline MergeWs merge_ws_layout(int B, int max_V) {
+    MergeWs w;
+    w.NCT = ceil_div(max_V, COS_BN);
+    size_t o = 0;
+    w.pruned_off = o; o += align_up((size_t)B * max_V * 4, 256);
+    w.rnorm_off = o;  o += align_up((size_t)B * max_V * 4, 256);
+    w.part_off = o;   o += align_up((size_t)B * w.NCT * max_V * 8, 256);
+    w.assign_off = o; o += align_up((size_t)B * max_V * 4, 256);
+    w.seg_off = o;    o += align_up((size_t)B * (max_V + 1) * 4, 256);
+    w.mem_off = o;    o += align_up((size_t)B * max_V * 4, 256);
+    w.total = o;
+    return w;
+}
+size_t merge_ws_bytes(int B, int max_V) { return merge_ws_layout(B, max_V).total; }
+
+struct SampleGeom { int tok0, N, vs, V, k, M; };
+__device__ __forceinline__ SampleGeom sample_geom(int b, const int32_t* seq_off, const int32_t* vis_start,
+                                                  const int32_t* vis_count, const int32_t* kept_off, int max_V, int max_keep) {
+    SampleGeom s;
+    s.tok0 = seq_off[b];
+    s.N = seq_off[b + 1] - s.tok0;
+    s.vs = min(max(vis_start[b], 0), s.N);
+    s.V = min(min(vis_count[b], max_V), s.N - s.vs);
+    s.k = min(min(kept_off[b + 1] - kept_off[b], max_keep), s.V);
+    s.M = s.V - s.k;
+    return s;
+}
+
+// exclusive workgroup scan of one int per thread (1024 threads)
+__device__ __forceinline__ int fin_excl_scan(int v, int* wsum /*[17]*/, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o, WAVE);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int w = 0; w < FIN_THREADS / 64; ++w) { const int t = wsum[w]; wsum[w] = run; run += t; }
+        wsum[16] = run;
+    }
+    __syncthreads();
+    *total = wsum[16];
+    return wsum[wave] + inc - v;
+}
+
+// ---- prep: ascending list of pruned visual tokens -------------------------------------------
+__global__ __launch_bounds__(FIN_THREADS) void merge_prep_kernel(
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
+    const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off, int max_V, int max_keep,
+    int32_t* __restrict__ pruned) {
+    extern __shared__ int lds[];          // flags [max_V]
+    __shared__ int wsum[17];
+    const int b = blockIdx.x;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    if (s.V <= 0) return;
+    for (int j = threadIdx.x; j < s.V; j += FIN_THREADS) lds[j] = 0;
+    __syncthreads();
+    for (int r = threadIdx.x; r < s.k; r += FIN_THREADS) lds[min(max(kept_idx[kept_off[b] + r], 0), s.V - 1)] = 1;
+    __syncthreads();
+    const int per = (s.V + FIN_THREADS - 1) / FIN_THREADS;
+    const int j0 = min((int)threadIdx.x * per, s.V), j1 = min(j0 + per, s.V);
+    int n = 0;
+    for (int j = j0; j < j1; ++j) n += (lds[j] == 0);
+    int tot;
+    int p = fin_excl_scan(n, wsum, &tot);
+    int32_t* out = pruned + (size_t)b * max_V;
+    for (int j = j0; j < j1; ++j)
+        if (lds[j] == 0) out[p++] = j;
+}
+
+// ---- norms: one wave per visual row --------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void merge_norms_kernel(
+    const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
+    const int32_t* __restrict__ vis_count, int max_V, float* __restrict__ rnorm) {
+    const int b = blockIdx.y;
+    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    const int tok0 = seq_off[b];
+    const int N = seq_off[b + 1] - tok0;
+    const int vs = min(max(vis_start[b], 0), N);
+    const int V = min(min(vis_count[b], max_V), N - vs);
+    if (j >= V) return;
+    const T* row = f + (size_t)(tok0 + vs + j) * d;
+    constexpr int EPC = 16 / sizeof(T);       // elements per 16-byte chunk
+    float ss = 0.f;
+    for (int c = lane; c < d / EPC; c += 64) {
+        const uint4 w = *reinterpret_cast<const uint4*>(row + (size_t)c * EPC);
+        if constexpr (sizeof(T) == 2) {
+            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { const float a = bf16_lo(ww[e]), c2 = bf16_hi(ww[e]); ss += a * a; ss += c2 * c2; }
+        } else {
+            const float a0 = __uint_as_float(w.x), a1 = __uint_as_float(w.y), a2 = __uint_as_float(w.z), a3 = __uint_as_float(w.w);
+            ss += a0 * a0; ss += a1 * a1; ss += a2 * a2; ss += a3 * a3;
+        }
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) rnorm[(size_t)b * max_V + j] = 1.0f / fmaxf(sqrtf(ss), 1e-15f);
+}
+
+// ---- cosine GEMM + fused argmax, bf16 MFMA ---------------------------------------------------
+// Workgroup tile: (TM*64) pruned rows x 128 kept slots, 4 waves as 2 x 2, wave tile (TM*32) x 64.
+template <int TM>
+__global__ __launch_bounds__(256) void cos_argmax_bf16(
+    const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
+    const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
+    float2* __restrict__ part) {
+    constexpr int BM = TM * 64;
+    constexpr int A_CH = BM * (COS_BK / 8) / 256;       // 16-byte chunks per thread, A tile
+    constexpr int B_CH = COS_BN * (COS_BK / 8) / 256;   // B tile
+    const int ct = blockIdx.x, rt = blockIdx.y, b = blockIdx.z;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    if (rt * BM >= s.M || ct * COS_BN >= s.k) return;
+
+    __shared__ __attribute__((aligned(16))) uint16_t As[BM * COS_LDA];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[COS_BN * COS_LDA];
+    __shared__ float rnA[BM], rnB[COS_BN];
+    __shared__ float2 red[2][BM];
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int c = lane & 31, g = lane >> 5;
+    const int32_t* pr = pruned + (size_t)b * max_V;
+    const int32_t* kp = kept_idx + kept_off[b];
+    const float* rn = rnorm + (size_t)b * max_V;
+    const size_t base = (size_t)(s.tok0 + s.vs) * d;
+
+    // per-thread source rows of the global -> LDS copy (rows past the end re-read row 0; masked later)
+    const uint16_t* a_src[A_CH];
+    const uint16_t* b_src[B_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) {
+        const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
+        const int p = rt * BM + row;
+        const int m = (p < s.M) ? pr[p] : pr[0];
+        a_src[i] = f + base + (size_t)m * d + cc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) {
+        const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
+        const int r = ct * COS_BN + row;
+        const int j = min(max(kp[(r < s.k) ? r : 0], 0), s.V - 1);
+        b_src[i] = f + base + (size_t)j * d + cc * 8;
+    }
+    for (int t = tid; t < BM; t += 256) { const int p = rt * BM + t; rnA[t] = (p < s.M) ? rn[pr[p]] : 0.f; }
+    for (int t = tid; t < COS_BN; t += 256) {
+        const int r = ct * COS_BN + t;
+        rnB[t] = (r < s.k) ? rn[min(max(kp[r], 0), s.V - 1)] : 0.f;
+    }
+
+    f32x16 acc[TM][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    uint4 a_reg[A_CH], b_reg[B_CH];
+#pragma unroll
+    for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4*>(a_src[i]);
+#pragma unroll
+    for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const uint4*>(b_src[i]);
+
+    const int nkt = d / COS_BK;
+    for (int kt = 0; kt < nkt; ++kt) {
+        __syncthreads();                                   // previous stage fully consumed
+#pragma unroll
+        for (int i = 0; i < A_CH; ++i) {
+            const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
+            *reinterpret_cast<uint4*>(&As[row * COS_LDA + cc * 8]) = a_reg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < B_CH; ++i) {
+            const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
+            *reinterpret_cast<uint4*>(&Bs[row * COS_LDA + cc * 8]) = b_reg[i];
+        }
+        __syncthreads();
+        if (kt + 1 < nkt) {
+            const int ko = (kt + 1) * COS_BK;
+#pragma unroll
+            for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4*>(a_src[i] + ko);
+#pragma unroll
+            for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const uint4*>(b_src[i] + ko);
+        }
+#pragma unroll
+        for (int kk = 0; kk < COS_BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[2];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * (TM * 32) + i * 32 + c) * COS_LDA + kk * 16 + g * 8]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + j * 32 + c) * COS_LDA + kk * 16 + g * 8]);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // epilogue: cosine = dot * rn_row * rn_col; per row, best (value, slot) over this tile's columns
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+            const float rr = rnA[row];
+            float bv = -INFINITY; int bi = 0x7FFFFFFF;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = wn * 64 + j * 32 + c;
+                const int slot = ct * COS_BN + col;
+                const float v = (slot < s.k) ? acc[i][j][e] * rr * rnB[col] : -INFINITY;
+                if (v > bv) { bv = v; bi = slot; }
+            }
+#pragma unroll
+            for (int o = 1; o < 32; o <<= 1) {
+                const float v2 = __shfl_xor(bv, o, WAVE);
+                const int i2 = __shfl_xor(bi, o, WAVE);
+                if (v2 > bv || (v2 == bv && i2 < bi)) { bv = v2; bi = i2; }
+            }
+            if (c == 0) red[wn][row] = make_float2(bv, __int_as_float(bi));
+        }
+    }
+    __syncthreads();
+    for (int t = tid; t < BM; t += 256) {
+        const int p = rt * BM + t;
+        if (p < s.M) {
+            float2 a = red[0][t];
+            const float2 b2 = red[1][t];
+            if (b2.x > a.x) a = b2;                       // equal values: lower slot (wn = 0) stays
+            part[((size_t)b * NCT + ct) * max_V + p] = a;
+        }
+    }
+}
+
+// ---- cosine + argmax, generic: one workgroup per pruned row, waves stride over the kept slots ---
+template <typename T>
+__global__ __launch_bounds__(256) void cos_argmax_generic(
+    const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
+    const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
+    float2* __restrict__ part) {
+    const int p = blockIdx.x, b = blockIdx.y;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    if (p >= s.M) return;
+    __shared__ float2 red[4];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int m = pruned[(size_t)b * max_V + p];
+    const int32_t* kp = kept_idx + kept_off[b];
+    const float* rn = rnorm + (size_t)b * max_V;
+    const T* xm = f + (size_t)(s.tok0 + s.vs + m) * d;
+    float bv = -INFINITY; int bi = 0x7FFFFFFF;
+    for (int r = wave; r < s.k; r += 4) {
+        const int j = min(max(kp[r], 0), s.V - 1);
+        const T* xk = f + (size_t)(s.tok0 + s.vs + j) * d;
+        float dot = 0.f;
+        for (int cidx = lane; cidx < d; cidx += 64) dot += Elem<T>::load(xm + cidx) * Elem<T>::load(xk + cidx);
+        dot = wave_sum(dot);
+        const float v = dot * rn[m] * rn[j];
+        if (v > bv) { bv = v; bi = r; }
+    }
+    if (lane == 0) red[wave] = make_float2(bv, __int_as_float(bi));
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float2 a = red[0];
+        for (int w = 1; w < 4; ++w) {
+            const float2 c2 = red[w];
+            if (c2.x > a.x || (c2.x == a.x && __float_as_int(c2.y) < __float_as_int(a.y))) a = c2;
+        }
+        part[((size_t)b * NCT + 0) * max_V + p] = a;
+    }
+}
+
+// ---- finalize: argmax over column tiles, CSR of all visual tokens by slot -------------------
+__global__ __launch_bounds__(FIN_THREADS) void merge_finalize_kernel(
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
+    const int32_t* __restrict__ vis_off, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float2* __restrict__ part, int NCT, int nct_used_per_128,
+    int32_t* __restrict__ assign_out, int32_t* __restrict__ assign_ws, int32_t* __restrict__ counts,
+    int32_t* __restrict__ seg_off, int32_t* __restrict__ members) {
+    extern __shared__ int lds[];      // off[max_keep + 1] | mem[max_V]
+    __shared__ int wsum[17];
+    const int b = blockIdx.x;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    if (s.V <= 0 || s.k <= 0) return;
+    int* off = lds;
+    int* mem = lds + (max_keep + 1);
+    const int tid = threadIdx.x;
+    const int32_t* pr = pruned + (size_t)b * max_V;
+    const int32_t* kp = kept_idx + kept_off[b];
+    int32_t* asg = assign_ws + (size_t)b * max_V;
+    int32_t* asg_out = assign_out ? assign_out + vis_off[b] : nullptr;
+    const int nct = nct_used_per_128 ? (s.k + COS_BN - 1) / COS_BN : 1;
+
+    for (int r = tid; r <= s.k; r += FIN_THREADS) off[r] = 0;
+    __syncthreads();
+    for (int p = tid; p < s.M; p += FIN_THREADS) {
+        float bv = -INFINITY; int bi = 0;
+        for (int ct = 0; ct < nct; ++ct) {
+            const float2 a = part[((size_t)b * NCT + ct) * max_V + p];
+            if (a.x > bv) { bv = a.x; bi = __float_as_int(a.y); }
+        }
+        bi = min(max(bi, 0), s.k - 1);
+        const int m = pr[p];
+        asg[m] = bi;
+        if (asg_out) asg_out[m] = bi;
+        atomicAdd(&off[bi], 1);
+    }
+    for (int r = tid; r < s.k; r += FIN_THREADS) {
+        const int j = min(max(kp[r], 0), s.V - 1);
+        asg[j] = r;
+        if (asg_out) asg_out[j] = r;
+        atomicAdd(&off[r], 1);
+    }
+    __syncthreads();
+    // exclusive scan of the slot histogram
+    const int per = (s.k + FIN_THREADS - 1) / FIN_THREADS;
+    const int r0 = min(tid * per, s.k), r1 = min(r0 + per, s.k);
+    int n = 0;
+    for (int r = r0; r < r1; ++r) n += off[r];
+    int tot;
+    int run = fin_excl_scan(n, wsum, &tot);
+    int32_t* so = seg_off + (size_t)b * (max_V + 1);
+    for (int r = r0; r < r1; ++r) {
+        const int cnt = off[r];
+        if (counts) counts[kept_off[b] + r] = cnt;
+        so[r] = run;
+        off[r] = run;
+        run += cnt;
+    }
+    if (tid == 0) so[s.k] = s.V;
+    __syncthreads();
+    // unordered fill (LDS cursor), then rank inside each segment to order the members ascending
+    for (int j = tid; j < s.V; j += FIN_THREADS) {
+        const int pos = atomicAdd(&off[asg[j]], 1);
+        mem[pos] = j;
+    }
+    __syncthreads();
+    int32_t* mo = members + (size_t)b * max_V;
+    for (int pos = tid; pos < s.V; pos += FIN_THREADS) {
+        const int j = mem[pos];
+        const int r = asg[j];
+        const int start = (r == 0) ? 0 : off[r - 1];      // off[r] now holds the END of segment r
+        const int end = off[r];
+        int rank = 0;
+        for (int q2 = start; q2 < end; ++q2) rank += (mem[q2] < j);
+        mo[start + rank] = j;
+    }
+}
+
+// ---- scatter-average + compaction ----------------------------------------------------------
+template <typename T, int CPT>     // CPT: 16-byte chunks per thread per pass
+__global__ __launch_bounds__(256) void merge_scatter_kernel(
+    const T* __restrict__ x, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
+    const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const int32_t* __restrict__ seg_off,
+    const int32_t* __restrict__ members, T* __restrict__ y, int32_t* __restrict__ src_pos) {
+    constexpr int EPC = 16 / sizeof(T);
+    const int o = blockIdx.x, b = blockIdx.y;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    const int N_m = s.N - s.M;
+    if (o >= N_m) return;
+    const int tid = threadIdx.x;
+    T* yrow = y + (size_t)(out_off[b] + o) * d;
+    const int nch = d / EPC;
+    int src = -1, start = 0, len = 1;
+    const int32_t* mo = members + (size_t)b * max_V;
+    if (o < s.vs) src = o;
+    else if (o >= s.vs + s.k) src = o + s.M;
+    else {
+        const int r = o - s.vs;
+        const int32_t* so = seg_off + (size_t)b * (max_V + 1);
+        start = so[r];
+        len = so[r + 1] - start;
+        if (tid == 0 && src_pos) src_pos[out_off[b] + o] = s.vs + min(max(kept_idx[kept_off[b] + r], 0), s.V - 1);
+        if (len <= 1) src = s.vs + mo[start];             // nothing absorbed: bit-exact copy
+    }
+    if (src >= 0) {
+        if (tid == 0 && src_pos && (o < s.vs || o >= s.vs + s.k)) src_pos[out_off[b] + o] = src;
+        const uint4* in = reinterpret_cast<const uint4*>(x + (size_t)(s.tok0 + src) * d);
+        uint4* out = reinterpret_cast<uint4*>(yrow);
+        for (int c = tid; c < nch; c += 256) out[c] = in[c];
+        return;
+    }
+    const T* xv = x + (size_t)(s.tok0 + s.vs) * d;
+    const float inv = (mode == D3TOM_MERGE_MEAN) ? (float)len : 1.0f;
+    for (int c0 = tid; c0 < nch; c0 += 256 * CPT) {
+        float acc[CPT][EPC];
+#pragma unroll
+        for (int u = 0; u < CPT; ++u)
+#pragma unroll
+            for (int e = 0; e < EPC; ++e) acc[u][e] = 0.f;
+        for (int t = 0; t < len; ++t) {
+            const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)mo[start + t] * d);
+#pragma unroll
+            for (int u = 0; u < CPT; ++u) {
+                const int c = c0 + 256 * u;
+                if (c < nch) {
+                    const uint4 w = row[c];
+                    if constexpr (sizeof(T) == 2) {
+                        acc[u][0] += bf16_lo(w.x); acc[u][1] += bf16_hi(w.x);
+                        acc[u][2] += bf16_lo(w.y); acc[u][3] += bf16_hi(w.y);
+                        acc[u][4] += bf16_lo(w.z); acc[u][5] += bf16_hi(w.z);
+                        acc[u][6] += bf16_lo(w.w); acc[u][7] += bf16_hi(w.w);
+                    } else {
+                        acc[u][0] += __uint_as_float(w.x); acc[u][1] += __uint_as_float(w.y);
+                        acc[u][2] += __uint_as_float(w.z); acc[u][3] += __uint_as_float(w.w);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            const int c = c0 + 256 * u;
+            if (c < nch) {
+                uint4 w;
+                if constexpr (sizeof(T) == 2) {
+                    w.x = pack_bf16x2(acc[u][0] / inv, acc[u][1] / inv);
+                    w.y = pack_bf16x2(acc[u][2] / inv, acc[u][3] / inv);
+                    w.z = pack_bf16x2(acc[u][4] / inv, acc[u][5] / inv);
+                    w.w = pack_bf16x2(acc[u][6] / inv, acc[u][7] / inv);
+                } else {
+                    w.x = __float_as_uint(acc[u][0] / inv); w.y = __float_as_uint(acc[u][1] / inv);
+                    w.z = __float_as_uint(acc[u][2] / inv); w.w = __float_as_uint(acc[u][3] / inv);
+                }
+                reinterpret_cast<uint4*>(yrow)[c] = w;
+            }
+        }
+    }
+}
+
+}  // namespace d3tom
+
+using namespace d3tom;
+
+extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
+                           int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
+                           const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
+                           int max_N, int max_V, int max_keep, int mode,
+                           const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
+                           void* ws, size_t ws_bytes, void* stream) {
+    if (!x || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off || !y)
+        return D3TOM_ERR_INVALID_ARG;
+    if (B < 1 || d < 1 || max_N < 1 || max_V < 1 || max_V > max_N || max_keep < 1 || max_keep > max_V)
+        return D3TOM_ERR_INVALID_ARG;
+    if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
+    if (mode != D3TOM_MERGE_MEAN && mode != D3TOM_MERGE_SUM) return D3TOM_ERR_INVALID_ARG;
+    const int epc = (dt == D3TOM_BF16) ? 8 : 4;
+    if (!sim) { sim = x; d_sim = d; }
+    if (d_sim < 1) return D3TOM_ERR_INVALID_ARG;
+    if ((d % epc) || (d_sim % epc)) return D3TOM_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(sim) || !aligned16(y)) return D3TOM_ERR_INVALID_ARG;
+    if (max_V > D3TOM_MAX_VISUAL) return D3TOM_ERR_UNSUPPORTED;
+    const MergeWs w = merge_ws_layout(B, max_V);
+    if (!ws) return D3TOM_ERR_INVALID_ARG;
+    if (ws_bytes < w.total || (((uintptr_t)ws) & 255u)) return D3TOM_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    char* wsb = (char*)ws;
+    int32_t* pruned = (int32_t*)(wsb + w.pruned_off);
+    float* rnorm = (float*)(wsb + w.rnorm_off);
+    float2* part = (float2*)(wsb + w.part_off);
+    int32_t* asg_ws = (int32_t*)(wsb + w.assign_off);
+    int32_t* seg = (int32_t*)(wsb + w.seg_off);
+    int32_t* mem = (int32_t*)(wsb + w.mem_off);
+
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)merge_prep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                D3TOM_MAX_VISUAL * 4) != hipSuccess ||
+            hipFuncSetAttribute((const void*)merge_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (2 * D3TOM_MAX_VISUAL + 1) * 4) != hipSuccess)
+            return D3TOM_ERR_DEVICE;
+        attr_set = true;
+    }
+
+    merge_prep_kernel<<<B, FIN_THREADS, (size_t)max_V * 4, st>>>(seq_off, vis_start, vis_count, kept_idx, kept_off, max_V,
+                                                                 max_keep, pruned);
+    D3TOM_LAUNCH_CHECK();
+    const dim3 gn(ceil_div(max_V, 4), B);
+    if (dt == D3TOM_BF16)
+        merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm);
+    else
+        merge_norms_kernel<float><<<gn, 256, 0, st>>>((const float*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm);
+    D3TOM_LAUNCH_CHECK();
+
+    const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0);
+    if (mfma) {
+        const int nct = ceil_div(max_keep, COS_BN);
+        // 128-row tiles unless that leaves most of the 256 CUs idle
+        const bool small = (long)nct * ceil_div(max_V, 128) * B < 384;
+        if (small) {
+            const dim3 g(nct, ceil_div(max_V, 64), B);
+            cos_argmax_bf16<1><<<g, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off,
+                                                  max_V, max_keep, pruned, rnorm, w.NCT, part);
+        } else {
+            const dim3 g(nct, ceil_div(max_V, 128), B);
+            cos_argmax_bf16<2><<<g, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off,
+                                                  max_V, max_keep, pruned, rnorm, w.NCT, part);
+        }
+    } else {
+        const dim3 g(max_V, B);
+        if (dt == D3TOM_BF16)
+            cos_argmax_generic<uint16_t><<<g, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx,
+                                                            kept_off, max_V, max_keep, pruned, rnorm, w.NCT, part);
+        else
+            cos_argmax_generic<float><<<g, 256, 0, st>>>((const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx,
+                                                         kept_off, max_V, max_keep, pruned, rnorm, w.NCT, part);
+    }
+    D3TOM_LAUNCH_CHECK();
+
+    merge_finalize_kernel<<<B, FIN_THREADS, (size_t)(max_keep + 1 + max_V) * 4, st>>>(
+        seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
+        assign, asg_ws, counts, seg, mem);
+    D3TOM_LAUNCH_CHECK();
+
+    const int max_Nm = max_N;      // upper bound on output rows per sample
+    const dim3 gs(max_Nm, B);
+    if (dt == D3TOM_BF16)
+        merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>((const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx,
+                                                              kept_off, max_V, max_keep, mode, out_off, seg, mem,
+                                                              (uint16_t*)y, src_pos);
+    else
+        merge_scatter_kernel<float, 2><<<gs, 256, 0, st>>>((const float*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off,
+                                                           max_V, max_keep, mode, out_off, seg, mem, (float*)y, src_pos);
+    D3TOM_LAUNCH_CHECK();
+    return D3TOM_OK;
+}

@@ -1,0 +1,144 @@
+// d3tom_select_topk: keep / merge partition (Section 3.2: V_kept = tokens whose score rank is at most
+// the kept count; Algorithm 1, the TopK line).
+//
+// One 1024-thread workgroup per sample, the whole score vector resident in LDS as order-preserving
+// 32-bit keys.  A 4 x 8-bit most-significant-digit radix SELECT finds the k-th largest key exactly
+// (no sort), then an ordered compaction emits the kept positions ascending.  Equal keys at the
+// threshold are taken lowest index first, which makes the selection identical to ranking by
+// (score descending, index ascending).  Integer LDS atomics only: deterministic.
+#include "common.hpp"
+
+namespace d3tom {
+
+constexpr int TOPK_THREADS = 1024;
+
+__device__ __forceinline__ uint32_t order_key(float f) {       // ascending uint order == ascending float order
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// exclusive prefix sum of one int per thread over the workgroup; returns the prefix, total in *total
+__device__ __forceinline__ int block_excl_scan(int v, int* wsum /*[17]*/, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o, WAVE);
+        if (lane >= o) inc += t;
+    }
+    __syncthreads();                       // wsum reuse
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int run = 0;
+        for (int w = 0; w < TOPK_THREADS / 64; ++w) { const int t = wsum[w]; wsum[w] = run; run += t; }
+        wsum[16] = run;
+    }
+    __syncthreads();
+    *total = wsum[16];
+    return wsum[wave] + inc - v;
+}
+
+__global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
+    const float* __restrict__ scores, const int32_t* __restrict__ score_off, const int32_t* __restrict__ keep_k,
+    const int32_t* __restrict__ kept_off, int max_V, int32_t* __restrict__ kept_idx, int32_t* __restrict__ slot_of) {
+    extern __shared__ uint32_t ukey[];                 // [max_V]
+    __shared__ int hist[256];
+    __shared__ int wsum[17];
+    __shared__ int sel[2];
+    const int b = blockIdx.x;
+    const int s0 = score_off[b];
+    const int V = min(score_off[b + 1] - s0, max_V);
+    if (V <= 0) return;
+    const int kk = min(max(keep_k[b], 1), V);
+    const int tid = threadIdx.x;
+
+    for (int j = tid; j < V; j += TOPK_THREADS) ukey[j] = order_key(scores[s0 + j]);
+    uint32_t prefix = 0, mask = 0;
+    int remaining = kk;
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int j = tid; j < V; j += TOPK_THREADS) {
+            const uint32_t u = ukey[j];
+            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        if (tid < 64) {
+            // lane l owns digits 255-4l .. 252-4l (descending); find the digit holding the remaining-th key
+            int c[4], tot = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { c[e] = hist[255 - (4 * tid + e)]; tot += c[e]; }
+            int inc = tot;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int t = __shfl_up(inc, o, WAVE);
+                if (tid >= o) inc += t;
+            }
+            int before = inc - tot;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (before < remaining && remaining <= before + c[e]) { sel[0] = 255 - (4 * tid + e); sel[1] = remaining - before; }
+                before += c[e];
+            }
+        }
+        __syncthreads();
+        prefix |= ((uint32_t)sel[0]) << shift;
+        mask |= 255u << shift;
+        remaining = sel[1];
+    }
+    const uint32_t thr = prefix;       // k-th largest key; `remaining` of the keys equal to it are kept
+    const int per = (V + TOPK_THREADS - 1) / TOPK_THREADS;
+    const int j0 = min(tid * per, V), j1 = min(j0 + per, V);
+    int n_eq = 0;
+    for (int j = j0; j < j1; ++j) n_eq += (ukey[j] == thr);
+    int tot_eq;
+    int eq_before = block_excl_scan(n_eq, wsum, &tot_eq);
+    int n_keep = 0;
+    {
+        int e = eq_before;
+        for (int j = j0; j < j1; ++j) {
+            const uint32_t u = ukey[j];
+            n_keep += (u > thr) || (u == thr && e < remaining);
+            e += (u == thr);
+        }
+    }
+    int tot_keep;
+    int slot = block_excl_scan(n_keep, wsum, &tot_keep);
+    const int k0 = kept_off[b];
+    int e = eq_before;
+    for (int j = j0; j < j1; ++j) {
+        const uint32_t u = ukey[j];
+        const bool keep = (u > thr) || (u == thr && e < remaining);
+        e += (u == thr);
+        slot_of[s0 + j] = keep ? slot : -1;
+        if (keep) { kept_idx[k0 + slot] = j; ++slot; }
+    }
+}
+
+}  // namespace d3tom
+
+using namespace d3tom;
+
+extern "C" int d3tom_select_topk(const float* scores, int B, const int32_t* score_off, const int32_t* keep_k,
+                                 const int32_t* kept_off, int max_V,
+                                 int32_t* kept_idx, int32_t* slot_of,
+                                 void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    if (!scores || !score_off || !keep_k || !kept_off || !kept_idx || !slot_of) return D3TOM_ERR_INVALID_ARG;
+    if (B < 1 || max_V < 1) return D3TOM_ERR_INVALID_ARG;
+    if (max_V > D3TOM_MAX_VISUAL) return D3TOM_ERR_UNSUPPORTED;
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute((const void*)topk_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                D3TOM_MAX_VISUAL * 4) != hipSuccess)
+            return D3TOM_ERR_DEVICE;
+        attr_set = true;
+    }
+    topk_select_kernel<<<B, TOPK_THREADS, (size_t)max_V * 4, (hipStream_t)stream>>>(scores, score_off, keep_k, kept_off,
+                                                                                    max_V, kept_idx, slot_of);
+    D3TOM_LAUNCH_CHECK();
+    return D3TOM_OK;
+}

@@ -1,0 +1,225 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2511_12280_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+if torch.cuda.is_available():
+    from paper_2511_12280_amd import binding as B
+    from parity import (GpuStep, check_assign, check_attend, check_full_sample, check_kept, check_merge,
+                        check_scores, gpu_attend)
+
+
+def _chain(samples, keeps, dtype, mode="mean", assign_rows=None, check=None):
+    step = GpuStep(samples, keeps, dtype, B.D3TOM_MERGE_MEAN if mode == "mean" else B.D3TOM_MERGE_SUM)
+    S = step.importance()
+    kept, slot = step.select_topk()
+    mout = step.merge()
+    stats = []
+    for b in (range(len(samples)) if check is None else check):
+        stats.append(check_full_sample(step, b, S, kept, slot, mout, assign_rows=assign_rows, mode=mode))
+    return step, S, kept, mout, stats
+
+
+# ---- the tiny fp32 layer: whole chain including the attention on the merged rows -------------------
+def test_tiny_f32_chain_with_attention():
+    wl = W.WORKLOADS["tiny_f32"]
+    g = W.SampleGen(wl)
+    s = g.step(16)
+    k = oracle.keep_count(wl.V, 0.25)
+    assert k == 36 and B.d3tom_keep_count(wl.V, 0.25) == 36
+    step, S, kept, mout, stats = _chain([s], [k], "f32")
+    assert stats[0]["kept_excused"] == 0 and stats[0]["assign_excused"] == 0
+    y = mout["y"][0]
+    assert y.shape == (100, 256)
+    q2, k2, v2 = g.proj.qkv(y)                       # projection of the merged rows (host, not on the path)
+    o = gpu_attend([(q2, k2, v2)], "f32")[0]
+    check_attend(o, q2, k2, v2, "f32")
+
+
+# ---- bf16 cases spanning several tiles with ragged tails ----------------------------------------------
+@pytest.mark.parametrize("P,V,O,H,dh,D,keep,mode", [
+    (37, 700, 40, 8, 128, 20, 0.23, "mean"),
+    (5, 333, 9, 4, 64, 3, 0.50, "mean"),
+    (0, 130, 17, 2, 128, 17, 0.10, "sum"),
+    (3, 1000, 70, 4, 128, 70, 0.77, "mean"),
+])
+def test_bf16_cases(P, V, O, H, dh, D, keep, mode):
+    c = W.random_case(100 + V, P + V + O, H * dh, H, P, V, D, dtype="bf16", centres=max(4, V // 6))
+    k = oracle.keep_count(V, keep)
+    _chain([c], [k], "bf16", mode=mode)
+
+
+def test_f32_generic_case_and_odd_head_size():
+    c = W.random_case(7, 150, 4 * 36, 4, 10, 120, 6, dtype="f32", centres=9)      # dh = 36
+    _chain([c], [oracle.keep_count(120, 0.3)], "f32")
+    c = W.random_case(8, 90, 2 * 40, 2, 4, 80, 5, dtype="bf16", centres=9)        # bf16 with dh = 40: generic kernels
+    _chain([c], [oracle.keep_count(80, 0.25)], "bf16")
+
+
+# ---- ragged batch ----------------------------------------------------------------------------------
+def test_ragged_batch_bf16():
+    shapes = [(20, 300, 30, 9, 0.2), (64, 513, 64, 33, 0.5), (1, 128, 5, 1, 0.1), (7, 129, 300, 100, 0.33), (0, 64, 2, 2, 1.0)]
+    samples, keeps = [], []
+    for i, (P, V, O, D, keep) in enumerate(shapes):
+        samples.append(W.random_case(200 + i, P + V + O, 4 * 128, 4, P, V, D, dtype="bf16", centres=max(3, V // 5)))
+        keeps.append(oracle.keep_count(V, keep))
+    step, S, kept, mout, stats = _chain(samples, keeps, "bf16")
+    # keep ratio 1: identity
+    np.testing.assert_array_equal(mout["y"][4], samples[4]["x"])
+    np.testing.assert_array_equal(kept[4], np.arange(64))
+
+
+# ---- top-k in isolation: exact, ties, extremes ---------------------------------------------------------
+def _topk_only(scores_list, ks):
+    V = [len(s) for s in scores_list]
+    lay = B.Layout(V, [0] * len(V), V, [[0]] * len(V), ks)
+    sc = torch.from_numpy(np.concatenate(scores_list).astype(np.float32)).cuda()
+    kept = torch.zeros(sum(ks), dtype=torch.int32, device="cuda")
+    slot = torch.zeros(sum(V), dtype=torch.int32, device="cuda")
+    B.d3tom_select_topk(sc, lay, kept, slot)
+    torch.cuda.synchronize()
+    return GpuStep.split(kept.cpu().numpy(), ks), GpuStep.split(slot.cpu().numpy(), V)
+
+
+def test_topk_exact_including_ties_and_extremes():
+    rng = np.random.default_rng(0)
+    cases = [
+        (rng.standard_normal(1).astype(np.float32), 1),
+        (rng.standard_normal(1000).astype(np.float32), 1),
+        (rng.standard_normal(1000).astype(np.float32), 1000),
+        (rng.random(3645).astype(np.float32), 365),
+        (np.round(rng.random(5000) * 8).astype(np.float32) / 8, 1234),          # heavy ties
+        (np.zeros(777, np.float32), 100),                                      # all equal: lowest indices
+        (np.concatenate([-rng.random(500), rng.random(500)]).astype(np.float32), 600),   # negative scores
+        (rng.random(B.D3TOM_MAX_VISUAL).astype(np.float32) * 1e-6, 4000),      # largest supported |V|
+        (np.float32(1.0) + rng.integers(0, 3, 4097).astype(np.float32) * np.float32(2 ** -23), 2048),  # 1-ulp apart
+    ]
+    kept, slot = _topk_only([c[0] for c in cases], [c[1] for c in cases])
+    for (s, k), kg, sg in zip(cases, kept, slot):
+        kr, sr = oracle.select_topk(s, k)
+        np.testing.assert_array_equal(kg, kr)
+        np.testing.assert_array_equal(sg, sr)
+
+
+# ---- attention in isolation ---------------------------------------------------------------------------
+@pytest.mark.parametrize("H,dh,dtype", [(4, 128, "bf16"), (3, 64, "bf16"), (2, 64, "f32"), (2, 40, "bf16")])
+def test_attend_varlen(H, dh, dtype):
+    lens = [1, 63, 64, 65, 200, 231, 493] if dh in (64, 128) and dtype == "bf16" else [1, 65, 300]
+    qkv = [W.random_qkv(300 + n, n, H, dh, dtype) for n in lens]
+    outs = gpu_attend(qkv, dtype)
+    for (q, k, v), o in zip(qkv, outs):
+        check_attend(o, q, k, v, dtype)
+
+
+def test_attend_special_cases_bf16():
+    q, k, v = W.random_qkv(5, 150, 2, 128, "bf16", spread=2.0)
+    v1 = np.broadcast_to(v[:1], v.shape).copy()
+    o = gpu_attend([(q, k, v1)], "bf16")[0]
+    np.testing.assert_allclose(o, v1, atol=1e-2)            # identical value rows come back (rows sum to one)
+    perm = np.random.default_rng(1).permutation(150)
+    o1 = gpu_attend([(q, k, v)], "bf16")[0]
+    o2 = gpu_attend([(q, k[perm], v[perm])], "bf16")[0]
+    np.testing.assert_allclose(o1, o2, atol=2e-2)           # no mask: key order is irrelevant
+
+
+# ---- full-size workloads ---------------------------------------------------------------------------------
+def test_llada_v_1024_full_chain():
+    wl = W.WORKLOADS["llada_v_1024"]
+    g = W.SampleGen(wl)
+    s = g.step(32)
+    k = oracle.keep_count(wl.V, 0.10)
+    assert k == 103
+    step, S, kept, mout, stats = _chain([s], [k], "bf16")
+    assert mout["y"][0].shape[0] == 231
+    q2, k2, v2 = g.proj.qkv(mout["y"][0])
+    o = gpu_attend([(q2, k2, v2)], "bf16")[0]
+    check_attend(o, q2, k2, v2, "bf16")
+    # also the 263-token length quoted for this workload
+    qkv = g.attention_inputs(263, 32)
+    check_attend(gpu_attend([qkv], "bf16")[0], *qkv, "bf16")
+
+
+@pytest.mark.parametrize("s_idx", [0, 31])
+def test_lavida_3645_sweep_steps_sampled(s_idx):
+    wl = W.WORKLOADS["lavida_3645_sweep"]
+    g = W.SampleGen(wl)
+    sch = W.sweep_schedule(wl)[s_idx]
+    s = g.step(sch["D"])
+    k = oracle.keep_count(wl.V, sch["keep_ratio"])
+    rng = np.random.default_rng(s_idx)
+    step = GpuStep([s], [k], "bf16")
+    S = step.importance(); kept, slot = step.select_topk(); mout = step.merge()
+    pruned = np.setdiff1d(np.arange(wl.V), kept[0])
+    rows = rng.choice(pruned, size=192, replace=False)
+    st = check_full_sample(step, 0, S, kept, slot, mout, assign_rows=rows)
+    n_m = wl.N - (wl.V - k)
+    assert mout["y"][0].shape[0] == n_m
+    qkv = g.attention_inputs(n_m, sch["D"])
+    o = gpu_attend([qkv], "bf16")[0]
+    check_attend(o, *qkv, "bf16", rows=rng.choice(n_m, size=48, replace=False))
+
+
+def test_serving_shape_ragged_subset():
+    wl = W.WORKLOADS["serving_b16"]
+    proj = W.Projections(wl)
+    draws = W.serving_draws(wl)[:3]
+    samples = [W.SampleGen(wl, proj, seed=dr["seed"]).step(dr["D"]) for dr in draws]
+    keeps = [oracle.keep_count(wl.V, dr["keep_ratio"]) for dr in draws]
+    rng = np.random.default_rng(3)
+    step = GpuStep(samples, keeps, "bf16")
+    S = step.importance(); kept, slot = step.select_topk(); mout = step.merge()
+    for b in range(len(samples)):
+        pruned = np.setdiff1d(np.arange(wl.V), kept[b])
+        check_full_sample(step, b, S, kept, slot, mout, assign_rows=rng.choice(pruned, size=96, replace=False))
+
+
+# ---- edge cases, determinism, error paths ---------------------------------------------------------------
+def test_edge_counts():
+    # k = 1 (everything merges into one token), D = 1, visual block at the very end
+    c = W.random_case(31, 80, 2 * 128, 2, 10, 70, 1, dtype="bf16", centres=3)
+    step, S, kept, mout, stats = _chain([c], [1], "bf16")
+    assert mout["counts"][0][0] == 70 and mout["y"][0].shape[0] == 11
+    # identical visual rows: every pruned token ties on all slots -> lowest slot takes all
+    c2 = W.random_case(32, 60, 128, 1, 5, 50, 2, dtype="bf16", centres=1, noise=0.0)
+    step, S, kept, mout, stats = _chain([c2], [5], "bf16")
+    np.testing.assert_array_equal(mout["counts"][0], [46, 1, 1, 1, 1])
+
+
+def test_bitwise_determinism():
+    c = W.random_case(41, 900, 4 * 128, 4, 30, 800, 12, dtype="bf16", centres=60)
+    k = oracle.keep_count(800, 0.2)
+    outs = []
+    for _ in range(2):
+        step = GpuStep([c], [k], "bf16")
+        S = step.importance(); kept, slot = step.select_topk(); m = step.merge()
+        outs.append((S[0].copy(), kept[0].copy(), m["y"][0].copy(), m["assign"][0].copy()))
+    for a, b in zip(outs[0], outs[1]):
+        np.testing.assert_array_equal(a, b)
+    qkv = W.random_qkv(42, 333, 4, 128, "bf16")
+    np.testing.assert_array_equal(gpu_attend([qkv], "bf16")[0], gpu_attend([qkv], "bf16")[0])
+
+
+def test_error_statuses():
+    c = W.random_case(51, 40, 128, 1, 4, 30, 2, dtype="bf16")
+    step = GpuStep([c], [5], "bf16")
+    lay0 = B.Layout([40], [4], [30], [[]], [5])                                # empty decider set
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_importance(step.q, step.k, lay0, 0.1, step.scores, step.ws_imp)
+    assert e.value.status == B.D3TOM_ERR_NO_DECIDERS
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_importance(step.q, step.k, step.lay, 0.1, step.scores, B.workspace(256))
+    assert e.value.status == B.D3TOM_ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_merge(step.x, None, step.lay, step.kept_idx, 7, step.y, None, None, None, step.ws_merge)
+    assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+    q = torch.zeros((8, 1, 300), dtype=torch.float32, device="cuda")           # head size above the limit
+    cu = torch.tensor([0, 8], dtype=torch.int32, device="cuda")
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_attend(q, q, q, cu, 8, 1.0, torch.zeros_like(q))
+    assert e.value.status == B.D3TOM_ERR_UNSUPPORTED
+    torch.cuda.synchronize()

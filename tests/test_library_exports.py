@@ -1,0 +1,62 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+host-only helpers agree with the paper's printed cost table and with the oracle's size rules."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2511_12280_amd", "libd3tom.so")
+HEADER = os.path.join(ROOT, "include", "d3tom.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2511_12280_amd import build
+        build.build()
+    return ctypes.CDLL(LIB)
+
+
+def test_every_declared_symbol_is_exported(lib):
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(d3tom_[a-z_0-9]+)\s*\(", text)))
+    assert {"d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_attend"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2511_12280_amd import binding
+    assert sorted(binding.EXPORTS) == names
+    for n in names:
+        assert callable(getattr(binding, n))
+
+
+def test_host_helpers(lib):
+    from paper_2511_12280_amd import binding as B
+    for V, r in [(144, 0.25), (1024, 0.10), (3645, 0.10), (3645, 0.5), (10, 0.0), (10, 1.0), (7, 3.0), (2304, 0.3141)]:
+        assert B.d3tom_keep_count(V, r) == oracle.keep_count(V, r)
+    assert B.d3tom_keep_count(0, 0.5) == 0
+    for s in range(32):
+        assert B.d3tom_schedule(s, 32, 0.1, 0.5) == pytest.approx(oracle.schedule(s, 32, 0.1, 0.5), abs=1e-15)
+    assert B.d3tom_status_string(0) == "ok" and "decider" in B.d3tom_status_string(2)
+    for op in range(4):
+        assert B.d3tom_workspace_bytes(op, 16, 2688, 2304, 32, 128, 256) >= 256
+    assert B.d3tom_workspace_bytes(9, 1, 10, 10, 1, 64, 1) == 0
+
+
+def test_cost_model_matches_printed_tables(lib):
+    from paper_2511_12280_amd import binding as B
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "paper_flops_tables.txt"))
+            if l.strip() and not l.startswith("#")]
+    for src, l_star, alpha, tf in rows:
+        got = B.d3tom_model_flops(float(alpha), int(l_star), 32, 32, 1000, 64, 64, 4096, 12288)
+        assert round(got / 1e12, 2) == pytest.approx(float(tf), abs=0.0051), (src, l_star, alpha)
+
+
+def test_device_entry_points_reject_bad_arguments_without_a_gpu(lib):
+    # null pointers are refused on the host before anything touches a device
+    lib.d3tom_attend.restype = ctypes.c_int
+    assert lib.d3tom_attend(None, None, None, 1, 1, None, 1, 1, 64, ctypes.c_float(1.0), None, None, ctypes.c_size_t(0), None) == 1
