@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the D3ToM hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input already resident in HBM:
+d3tom_importance -> d3tom_select_topk -> d3tom_merge -> d3tom_attend (the attention runs on
+pre-generated q/k/v of the merged length; the projection between merge and attention is not on the path).
+
+Prints ONE JSON line: denoise steps/s of the workload the metric is quoted on (the 3645-visual-token
+LaViDa-like sweep; the 1024-token LLaDA-V-like step is reported beside it under "also"), the roofline
+figure of the dominant kernel (HIP-event timings taken live, algorithmic bytes / flops from the shapes),
+and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np
+import torch
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+
+
+def build_steps(wl_name: str):
+    """Generate every step of the workload on the host and upload it.  Returns (workload, list of step dicts)."""
+    from paper_2511_12280_amd import binding as B
+    from paper_2511_12280_amd import workloads as W
+    wl = W.WORKLOADS[wl_name]
+    steps = []
+    if wl.B == 1:
+        g = W.SampleGen(wl)
+        for sch in W.sweep_schedule(wl):
+            s = g.step(sch["D"])
+            k = B.d3tom_keep_count(wl.V, sch["keep_ratio"])
+            n_m = wl.N - (wl.V - k)
+            steps.append(dict(samples=[s], keeps=[k], attn=[g.attention_inputs(n_m, sch["D"])], sch=sch))
+    else:
+        proj = W.Projections(wl)
+        samples, keeps, attn = [], [], []
+        for dr in W.serving_draws(wl):
+            g = W.SampleGen(wl, proj, seed=dr["seed"])
+            samples.append(g.step(dr["D"]))
+            k = B.d3tom_keep_count(wl.V, dr["keep_ratio"])
+            keeps.append(k)
+            attn.append(g.attention_inputs(wl.N - (wl.V - k), dr["D"]))
+        steps.append(dict(samples=samples, keeps=keeps, attn=attn, sch=dict(step=0)))
+    dev = []
+    for st in steps:
+        sm = st["samples"]
+        lay = B.Layout([s["N"] for s in sm], [s["vis_start"] for s in sm], [s["V"] for s in sm],
+                       [s["dec_idx"] for s in sm], st["keeps"])
+        cat = lambda key: np.concatenate([s[key] for s in sm], axis=0)
+        d = dict(lay=lay, q=B.to_device(cat("q"), wl.dtype), k=B.to_device(cat("k"), wl.dtype),
+                 x=B.to_device(cat("x"), wl.dtype),
+                 qa=B.to_device(np.concatenate([a[0] for a in st["attn"]]), wl.dtype),
+                 ka=B.to_device(np.concatenate([a[1] for a in st["attn"]]), wl.dtype),
+                 va=B.to_device(np.concatenate([a[2] for a in st["attn"]]), wl.dtype),
+                 cu=torch.from_numpy(np.concatenate([[0], np.cumsum(lay.Nm)]).astype(np.int32)).cuda(),
+                 host=st)
+        dev.append(d)
+    return wl, dev
+
+
+class Runner:
+    """Shared output buffers + workspaces, and the four launches of one step."""
+
+    def __init__(self, wl, dev):
+        from paper_2511_12280_amd import binding as B
+        self.B, self.wl, self.dev = B, wl, dev
+        mx = lambda f: max(f(d["lay"]) for d in dev)
+        tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+        self.scores = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.float32, device="cuda")
+        self.kept = torch.zeros(mx(lambda l: l.sum_keep), dtype=torch.int32, device="cuda")
+        self.slot = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.int32, device="cuda")
+        self.y = torch.zeros((mx(lambda l: l.sum_Nm), wl.d), dtype=tdt, device="cuda")
+        self.counts = torch.zeros(mx(lambda l: l.sum_keep), dtype=torch.int32, device="cuda")
+        self.src = torch.zeros(mx(lambda l: l.sum_Nm), dtype=torch.int32, device="cuda")
+        self.o = torch.zeros((mx(lambda l: l.sum_Nm), wl.H, wl.dh), dtype=tdt, device="cuda")
+        nb, mN, mV, mD = mx(lambda l: l.B), mx(lambda l: l.max_N), mx(lambda l: l.max_V), mx(lambda l: l.max_D)
+        self.ws_imp = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_IMPORTANCE, nb, mN, mV, wl.H, wl.dh, mD))
+        self.ws_merge = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_MERGE, nb, mN, mV, wl.H, wl.dh, mD))
+        self.scale = 1.0 / float(np.sqrt(wl.dh))
+
+    def step(self, i: int):
+        B, d = self.B, self.dev[i % len(self.dev)]
+        lay = d["lay"]
+        B.d3tom_importance(d["q"], d["k"], lay, self.scale, self.scores, self.ws_imp)
+        B.d3tom_select_topk(self.scores, lay, self.kept, self.slot)
+        B.d3tom_merge(d["x"], None, lay, self.kept, B.D3TOM_MERGE_MEAN, self.y, None, self.counts, self.src, self.ws_merge)
+        B.d3tom_attend(d["qa"], d["ka"], d["va"], d["cu"], lay.max_Nm, self.scale, self.o)
+
+
+def algorithmic(wl, lay):
+    """Per-kernel algorithmic bytes and flops of ONE launch for this batch layout (what the method must
+    move / compute: K once per sweep, the visual rows once, input + output rows once, 4 n^2 d for attention)."""
+    eb = 4 if wl.dtype == "f32" else 2
+    d = wl.d
+    out = {k: [0.0, 0.0] for k in ("imp_stats", "imp_scores", "topk_select", "merge_prep", "merge_norms",
+                                   "cos_argmax", "merge_finalize", "merge_scatter", "attend")}
+    for N, V, k, D, Nm in zip(lay.N, lay.V, lay.keep, lay.D, lay.Nm):
+        M = V - k
+        out["imp_stats"][0] += (N + D) * d * eb;            out["imp_stats"][1] += 2.0 * D * N * d
+        out["imp_scores"][0] += (V + D) * d * eb + 4 * V;   out["imp_scores"][1] += 2.0 * D * V * d
+        out["topk_select"][0] += 4 * V + 4 * k + 4 * V
+        out["merge_prep"][0] += 4 * k + 4 * M
+        out["merge_norms"][0] += V * d * eb + 4 * V
+        out["cos_argmax"][0] += V * d * eb;                 out["cos_argmax"][1] += 2.0 * M * k * d
+        out["merge_finalize"][0] += 8 * M + 12 * V
+        out["merge_scatter"][0] += (N + Nm) * d * eb + 4 * V
+        out["attend"][0] += 4 * Nm * d * eb;                out["attend"][1] += 4.0 * Nm * Nm * d
+    return out
+
+
+def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
+    from paper_2511_12280_amd import binding as B
+    t0 = time.time()
+    wl, dev = build_steps(wl_name)
+    gen_s = time.time() - t0
+    r = Runner(wl, dev)
+    for i in range(warmup):
+        r.step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        r.step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # the same K steps again with HIP events around every kernel launch
+    B.d3tom_profile_enable(True)
+    for i in range(steps):
+        r.step(i)
+    torch.cuda.synchronize()
+    prof = B.d3tom_profile_collect()
+    B.d3tom_profile_enable(False)
+    alg = {k: [0.0, 0.0] for k in prof}
+    for i in range(steps):
+        a = algorithmic(wl, dev[i % len(dev)]["lay"])
+        for k in alg:
+            alg[k][0] += a[k][0]; alg[k][1] += a[k][1]
+    kernels = {}
+    for k, (ms, calls) in prof.items():
+        if calls == 0:
+            continue
+        by, fl = alg[k]
+        t = ms * 1e-3
+        hbm_t, mfma_t = by / (PEAK_HBM_GBS * 1e9), fl / (PEAK_BF16_TFLOPS * 1e12)
+        bound = "mfma" if mfma_t > hbm_t else "hbm"
+        ach = (fl / t / 1e12) if bound == "mfma" else (by / t / 1e9)
+        peak = PEAK_BF16_TFLOPS if bound == "mfma" else PEAK_HBM_GBS
+        kernels[k] = dict(avg_us=round(ms * 1e3 / calls, 3), launches=calls, bound=bound, achieved=round(ach, 2),
+                          peak=peak, unit="TFLOP/s" if bound == "mfma" else "GB/s", frac=round(ach / peak, 4),
+                          share=0.0)
+    tot_ms = sum(ms for ms, c in prof.values())
+    for k in kernels:
+        kernels[k]["share"] = round(prof[k][0] / tot_ms, 4)
+    dom = max(kernels, key=lambda k: prof[k][0])
+    merge_us = sum(prof[k][0] for k in prof if k != "attend") * 1e3 / steps
+    attend_us = prof["attend"][0] * 1e3 / steps
+    res = dict(workload=wl_name, steps_per_s=steps / elapsed, ms_per_step=elapsed * 1e3 / steps,
+               merge_layer_us=round(merge_us, 2), attend_us=round(attend_us, 2), kernels=kernels, dominant=dom,
+               gen_s=round(gen_s, 1))
+    if cpu_baseline:
+        res["cpu_baseline"] = oracle_baseline(wl, dev[0])
+    return wl, res
+
+
+def oracle_baseline(wl, d0):
+    """The fp64 oracle on one step of the workload (its first), all five stages, on the host cores."""
+    import oracle
+    st = d0["host"]
+    s, k, (qa, ka, va) = st["samples"][0], st["keeps"][0], st["attn"][0]
+    t0 = time.perf_counter()
+    oracle.merge_layer(s["q"], s["k"], s["x"], s["dec_idx"], s["vis_start"], s["V"], k)
+    oracle.attend(qa, ka, va)
+    t = time.perf_counter() - t0
+    per_step = t * (len(st["samples"]))       # batched workload: scale the one sample to the batch
+    return dict(value=round(1.0 / per_step, 5), unit="steps/s", cores=oracle.threads(), kind="oracle",
+                sample=f"first sample of step 0 ({s['D']} deciders, {k} kept of {s['V']}, attention over "
+                       f"{qa.shape[0]} tokens), all five stages, {t:.1f} s")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="lavida_3645_sweep")
+    ap.add_argument("--also", default="llada_v_1024", help="second workload reported beside the first ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the path is a single-GPU kernel chain (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    wl, res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
+    dom = res["kernels"][res["dominant"]]
+    line = {
+        "metric": "denoise steps/sec of the hot path (merge layer + bidirectional attention over the merged sequence)",
+        "value": round(res["steps_per_s"], 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": f"{wl.name}: {wl.V} visual + {wl.P} prompt + {wl.O} response tokens, hidden {wl.d}, "
+                               f"{wl.H}x{wl.dh} heads, batch {wl.B}, {wl.note}", "timed": "inputs resident in HBM"},
+        "merge_layer_us": res["merge_layer_us"], "attend_us": res["attend_us"],
+        "roofline": {"kernel": res["dominant"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
+                     "unit": dom["unit"], "frac": dom["frac"], "traffic": None, "avg_us": dom["avg_us"]},
+        "kernels": res["kernels"],
+    }
+    if "cpu_baseline" in res:
+        line["cpu_baseline"] = res["cpu_baseline"]
+    if args.also:
+        _, r2 = run_workload(args.also, args.steps, args.warmup, False)
+        line["also"] = {args.also: {"steps_per_s": round(r2["steps_per_s"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
+                                    "merge_layer_us": r2["merge_layer_us"], "attend_us": r2["attend_us"],
+                                    "kernels": r2["kernels"]}}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -189,6 +189,18 @@ int d3tom_attend(const void* q, const void* k, const void* v, int dt,
                  int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
                  void* o, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Per-kernel timing (diagnostics; used by the benchmark for its roofline figures).  While enabled,
+ * every kernel launch of the four entry points is bracketed by HIP events on the caller's stream.
+ * d3tom_profile_collect waits for the recorded events, adds up milliseconds and launch counts per
+ * kernel into the host arrays ms_sum[n] / calls[n] (n >= d3tom_profile_kernel_count()), and
+ * forgets the records.  Not thread-safe with respect to concurrent launches.
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_profile_enable(int on);
+int d3tom_profile_kernel_count(void);
+const char* d3tom_profile_kernel_name(int kernel);
+int d3tom_profile_collect(double* ms_sum /* host */, long long* calls /* host */, int n);
+
 #ifdef __cplusplus
 }
 #endif

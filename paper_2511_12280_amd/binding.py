@@ -30,7 +30,8 @@ D3TOM_OP_IMPORTANCE, D3TOM_OP_SELECT_TOPK, D3TOM_OP_MERGE, D3TOM_OP_ATTEND = ran
 D3TOM_MAX_VISUAL, D3TOM_MAX_DECIDERS = 16384, 256
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
-           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_attend"]
+           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_attend",
+           "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
 _vp, _i, _f, _d, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_double, ctypes.c_size_t
 _lib.d3tom_keep_count.restype = _i
@@ -53,6 +54,15 @@ _lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, 
                              _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
+
+
+_lib.d3tom_profile_enable.restype = _i
+_lib.d3tom_profile_enable.argtypes = [_i]
+_lib.d3tom_profile_kernel_count.restype = _i
+_lib.d3tom_profile_kernel_name.restype = ctypes.c_char_p
+_lib.d3tom_profile_kernel_name.argtypes = [_i]
+_lib.d3tom_profile_collect.restype = _i
+_lib.d3tom_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_longlong), _i]
 
 
 class D3tomError(RuntimeError):
@@ -106,6 +116,27 @@ def d3tom_workspace_bytes(op: int, B: int, max_N: int, max_V: int, H: int, dh: i
 
 def d3tom_status_string(status: int) -> str:
     return _lib.d3tom_status_string(int(status)).decode()
+
+
+def d3tom_profile_enable(on: bool) -> None:
+    _check(_lib.d3tom_profile_enable(1 if on else 0), "d3tom_profile_enable")
+
+
+def d3tom_profile_kernel_count() -> int:
+    return int(_lib.d3tom_profile_kernel_count())
+
+
+def d3tom_profile_kernel_name(kernel: int) -> str:
+    return _lib.d3tom_profile_kernel_name(int(kernel)).decode()
+
+
+def d3tom_profile_collect() -> dict:
+    """{kernel name: (total ms, launches)} since the last collect."""
+    n = d3tom_profile_kernel_count()
+    ms = (ctypes.c_double * n)()
+    calls = (ctypes.c_longlong * n)()
+    _check(_lib.d3tom_profile_collect(ms, calls, n), "d3tom_profile_collect")
+    return {d3tom_profile_kernel_name(i): (float(ms[i]), int(calls[i])) for i in range(n)}
 
 
 # ---- batch metadata (device int32 arrays + the host-known maxima the launches need) -------------

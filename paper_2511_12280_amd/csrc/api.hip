@@ -1,6 +1,29 @@
 // Host-only entry points of libd3tom: sizes, schedule, cost model, status names.
 #include <math.h>
+#include <mutex>
+#include <vector>
 #include "common.hpp"
+
+namespace d3tom { namespace prof {
+bool g_enabled = false;
+namespace {
+struct Rec { int kernel; hipEvent_t e0, e1; };
+std::vector<Rec> g_recs;
+std::mutex g_mu;
+}
+void mark_begin(int kernel, hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    Rec r; r.kernel = kernel; r.e0 = nullptr; r.e1 = nullptr;
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) return;
+    (void)hipEventRecord(r.e0, st);
+    g_recs.push_back(r);
+}
+void mark_end(int kernel, hipStream_t st) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (size_t i = g_recs.size(); i-- > 0;)
+        if (g_recs[i].kernel == kernel) { (void)hipEventRecord(g_recs[i].e1, st); return; }
+}
+}}  // namespace d3tom::prof
 
 namespace d3tom {
 size_t importance_ws_bytes(int B, int max_N, int max_V, int H, int dh, int max_D);
@@ -42,6 +65,36 @@ extern "C" size_t d3tom_workspace_bytes(int op, int B, int max_N, int max_V, int
         case D3TOM_OP_ATTEND: return 256;
         default: return 0;
     }
+}
+
+extern "C" int d3tom_profile_enable(int on) {
+    d3tom::prof::g_enabled = (on != 0);
+    return D3TOM_OK;
+}
+
+extern "C" int d3tom_profile_kernel_count(void) { return d3tom::prof::NUM_KERNELS; }
+
+extern "C" const char* d3tom_profile_kernel_name(int kernel) {
+    static const char* names[] = {"imp_stats", "imp_scores", "topk_select", "merge_prep", "merge_norms",
+                                  "cos_argmax", "merge_finalize", "merge_scatter", "attend"};
+    return (kernel >= 0 && kernel < d3tom::prof::NUM_KERNELS) ? names[kernel] : "";
+}
+
+extern "C" int d3tom_profile_collect(double* ms_sum, long long* calls, int n) {
+    using namespace d3tom::prof;
+    if (!ms_sum || !calls || n < NUM_KERNELS) return D3TOM_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (int i = 0; i < n; ++i) { ms_sum[i] = 0.0; calls[i] = 0; }
+    int status = D3TOM_OK;
+    for (auto& r : g_recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.e1) == hipSuccess && hipEventElapsedTime(&ms, r.e0, r.e1) == hipSuccess) {
+            ms_sum[r.kernel] += ms; calls[r.kernel] += 1;
+        } else status = D3TOM_ERR_DEVICE;
+        (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1);
+    }
+    g_recs.clear();
+    return status;
 }
 
 extern "C" const char* d3tom_status_string(int status) {

@@ -271,20 +271,19 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
     if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
         const dim3 g(ceil_div(max_seqlen, ATT_BQ), H, B);
         if (dh == 128)
-            attend_bf16_kernel<128><<<g, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H,
-                                                       scale2, (uint16_t*)o);
+            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<128><<<g, 256, 0, st>>>(
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, scale2, (uint16_t*)o));
         else
-            attend_bf16_kernel<64><<<g, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H,
-                                                      scale2, (uint16_t*)o);
+            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<64><<<g, 256, 0, st>>>(
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, scale2, (uint16_t*)o));
     } else {
         const dim3 g(max_seqlen, H, B);
         if (dt == D3TOM_F32)
-            attend_generic_kernel<float><<<g, 256, 0, st>>>((const float*)q, (const float*)k, (const float*)v, cu_seqlens, H, dh,
-                                                            scale2, (float*)o);
+            D3TOM_LAUNCH(ATTEND, st, attend_generic_kernel<float><<<g, 256, 0, st>>>(
+                (const float*)q, (const float*)k, (const float*)v, cu_seqlens, H, dh, scale2, (float*)o));
         else
-            attend_generic_kernel<uint16_t><<<g, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
-                                                               cu_seqlens, H, dh, scale2, (uint16_t*)o);
+            D3TOM_LAUNCH(ATTEND, st, attend_generic_kernel<uint16_t><<<g, 256, 0, st>>>(
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, dh, scale2, (uint16_t*)o));
     }
-    D3TOM_LAUNCH_CHECK();
     return D3TOM_OK;
 }

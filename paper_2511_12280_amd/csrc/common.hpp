@@ -70,9 +70,35 @@ __host__ __device__ __forceinline__ size_t align_up(size_t a, size_t b) { return
 // host-side argument checks
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 
+// ---- optional per-kernel timing (d3tom_profile_*): HIP events around each launch when enabled ----
+namespace prof {
+enum Kernel {
+    IMP_STATS = 0, IMP_SCORES, TOPK_SELECT, MERGE_PREP, MERGE_NORMS, COS_ARGMAX, MERGE_FINALIZE, MERGE_SCATTER, ATTEND,
+    NUM_KERNELS
+};
+extern bool g_enabled;
+void mark_begin(int kernel, hipStream_t st);
+void mark_end(int kernel, hipStream_t st);
+struct Scope {
+    int kernel; hipStream_t st;
+    Scope(int k, hipStream_t s) : kernel(k), st(s) { if (g_enabled) mark_begin(k, s); }
+    ~Scope() { if (g_enabled) mark_end(kernel, st); }
+};
+}  // namespace prof
+
 #define D3TOM_LAUNCH_CHECK()                                         \
     do {                                                             \
         if (hipGetLastError() != hipSuccess) return D3TOM_ERR_DEVICE; \
+    } while (0)
+
+// launch one kernel (timed when profiling is on) and turn a rejected launch into a status
+#define D3TOM_LAUNCH(KERNEL_ID, STREAM, ...)                         \
+    do {                                                             \
+        {                                                            \
+            prof::Scope _scope(prof::KERNEL_ID, STREAM);             \
+            __VA_ARGS__;                                             \
+        }                                                            \
+        D3TOM_LAUNCH_CHECK();                                        \
     } while (0)
 
 }  // namespace d3tom

@@ -330,40 +330,37 @@ extern "C" int d3tom_importance(const void* q, const void* k, int dt,
         float* sp = (float*)(wsb + w.sp_off);
         int* cnt = (int*)(wsb + w.cnt_off);
         const dim3 g1(w.NCH, H, B), g2(w.NCHV, H, B);
+        const uint16_t* qq = (const uint16_t*)q;
+        const uint16_t* kk = (const uint16_t*)k;
         if (dh == 128) {
-            imp_stats_bf16<128><<<g1, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
-                                                    dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV);
-            D3TOM_LAUNCH_CHECK();
-            imp_scores_bf16<128><<<g2, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
-                                                     dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
-                                                     w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores);
+            D3TOM_LAUNCH(IMP_STATS, st, imp_stats_bf16<128><<<g1, 256, 0, st>>>(
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV));
+            D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<128><<<g2, 256, 0, st>>>(
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
+                w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores));
         } else {
-            imp_stats_bf16<64><<<g1, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
-                                                   dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV);
-            D3TOM_LAUNCH_CHECK();
-            imp_scores_bf16<64><<<g2, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, scale2, seq_off, dec_idx,
-                                                    dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
-                                                    w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores);
+            D3TOM_LAUNCH(IMP_STATS, st, imp_stats_bf16<64><<<g1, 256, 0, st>>>(
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV));
+            D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<64><<<g2, 256, 0, st>>>(
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
+                w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores));
         }
-        D3TOM_LAUNCH_CHECK();
         return D3TOM_OK;
     }
     float* cws = (float*)(wsb + w.c_off);
     const dim3 g1(max_D, H, B), g2(ceil_div(max_V, 256), B);
     if (dt == D3TOM_F32) {
-        imp_stats_generic<float><<<g1, 256, 0, st>>>((const float*)q, (const float*)k, H, dh, scale2, seq_off, dec_idx,
-                                                     dec_off, max_D, cws);
-        D3TOM_LAUNCH_CHECK();
-        imp_scores_generic<float><<<g2, 256, 0, st>>>((const float*)q, (const float*)k, H, dh, scale2, seq_off, dec_idx,
-                                                      dec_off, vis_start, vis_count, score_off, max_D, max_V, cws, scores);
+        D3TOM_LAUNCH(IMP_STATS, st, imp_stats_generic<float><<<g1, 256, 0, st>>>(
+            (const float*)q, (const float*)k, H, dh, scale2, seq_off, dec_idx, dec_off, max_D, cws));
+        D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_generic<float><<<g2, 256, 0, st>>>(
+            (const float*)q, (const float*)k, H, dh, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, score_off,
+            max_D, max_V, cws, scores));
     } else {
-        imp_stats_generic<uint16_t><<<g1, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, dh, scale2, seq_off,
-                                                        dec_idx, dec_off, max_D, cws);
-        D3TOM_LAUNCH_CHECK();
-        imp_scores_generic<uint16_t><<<g2, 256, 0, st>>>((const uint16_t*)q, (const uint16_t*)k, H, dh, scale2, seq_off,
-                                                         dec_idx, dec_off, vis_start, vis_count, score_off, max_D, max_V,
-                                                         cws, scores);
+        D3TOM_LAUNCH(IMP_STATS, st, imp_stats_generic<uint16_t><<<g1, 256, 0, st>>>(
+            (const uint16_t*)q, (const uint16_t*)k, H, dh, scale2, seq_off, dec_idx, dec_off, max_D, cws));
+        D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_generic<uint16_t><<<g2, 256, 0, st>>>(
+            (const uint16_t*)q, (const uint16_t*)k, H, dh, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count,
+            score_off, max_D, max_V, cws, scores));
     }
-    D3TOM_LAUNCH_CHECK();
     return D3TOM_OK;
 }

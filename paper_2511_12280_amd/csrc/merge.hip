@@ -513,15 +513,15 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
         attr_set = true;
     }
 
-    merge_prep_kernel<<<B, FIN_THREADS, (size_t)max_V * 4, st>>>(seq_off, vis_start, vis_count, kept_idx, kept_off, max_V,
-                                                                 max_keep, pruned);
-    D3TOM_LAUNCH_CHECK();
+    D3TOM_LAUNCH(MERGE_PREP, st, merge_prep_kernel<<<B, FIN_THREADS, (size_t)max_V * 4, st>>>(
+        seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned));
     const dim3 gn(ceil_div(max_V, 4), B);
     if (dt == D3TOM_BF16)
-        merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm);
+        D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>(
+            (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm));
     else
-        merge_norms_kernel<float><<<gn, 256, 0, st>>>((const float*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm);
-    D3TOM_LAUNCH_CHECK();
+        D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<float><<<gn, 256, 0, st>>>(
+            (const float*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm));
 
     const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0);
     if (mfma) {
@@ -530,38 +530,39 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
         const bool small = (long)nct * ceil_div(max_V, 128) * B < 384;
         if (small) {
             const dim3 g(nct, ceil_div(max_V, 64), B);
-            cos_argmax_bf16<1><<<g, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off,
-                                                  max_V, max_keep, pruned, rnorm, w.NCT, part);
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 256, 0, st>>>(
+                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, w.NCT, part));
         } else {
             const dim3 g(nct, ceil_div(max_V, 128), B);
-            cos_argmax_bf16<2><<<g, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off,
-                                                  max_V, max_keep, pruned, rnorm, w.NCT, part);
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 256, 0, st>>>(
+                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, w.NCT, part));
         }
     } else {
         const dim3 g(max_V, B);
         if (dt == D3TOM_BF16)
-            cos_argmax_generic<uint16_t><<<g, 256, 0, st>>>((const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx,
-                                                            kept_off, max_V, max_keep, pruned, rnorm, w.NCT, part);
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_generic<uint16_t><<<g, 256, 0, st>>>(
+                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, w.NCT, part));
         else
-            cos_argmax_generic<float><<<g, 256, 0, st>>>((const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx,
-                                                         kept_off, max_V, max_keep, pruned, rnorm, w.NCT, part);
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_generic<float><<<g, 256, 0, st>>>(
+                (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, w.NCT, part));
     }
-    D3TOM_LAUNCH_CHECK();
 
-    merge_finalize_kernel<<<B, FIN_THREADS, (size_t)(max_keep + 1 + max_V) * 4, st>>>(
+    D3TOM_LAUNCH(MERGE_FINALIZE, st, merge_finalize_kernel<<<B, FIN_THREADS, (size_t)(max_keep + 1 + max_V) * 4, st>>>(
         seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
-        assign, asg_ws, counts, seg, mem);
-    D3TOM_LAUNCH_CHECK();
+        assign, asg_ws, counts, seg, mem));
 
-    const int max_Nm = max_N;      // upper bound on output rows per sample
-    const dim3 gs(max_Nm, B);
+    const dim3 gs(max_N, B);      // upper bound on output rows per sample; surplus workgroups exit at once
     if (dt == D3TOM_BF16)
-        merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>((const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx,
-                                                              kept_off, max_V, max_keep, mode, out_off, seg, mem,
-                                                              (uint16_t*)y, src_pos);
+        D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>(
+            (const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, seg,
+            mem, (uint16_t*)y, src_pos));
     else
-        merge_scatter_kernel<float, 2><<<gs, 256, 0, st>>>((const float*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off,
-                                                           max_V, max_keep, mode, out_off, seg, mem, (float*)y, src_pos);
-    D3TOM_LAUNCH_CHECK();
+        D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<float, 2><<<gs, 256, 0, st>>>(
+            (const float*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, seg, mem,
+            (float*)y, src_pos));
     return D3TOM_OK;
 }

@@ -137,8 +137,8 @@ extern "C" int d3tom_select_topk(const float* scores, int B, const int32_t* scor
             return D3TOM_ERR_DEVICE;
         attr_set = true;
     }
-    topk_select_kernel<<<B, TOPK_THREADS, (size_t)max_V * 4, (hipStream_t)stream>>>(scores, score_off, keep_k, kept_off,
-                                                                                    max_V, kept_idx, slot_of);
-    D3TOM_LAUNCH_CHECK();
+    hipStream_t st = (hipStream_t)stream;
+    D3TOM_LAUNCH(TOPK_SELECT, st, topk_select_kernel<<<B, TOPK_THREADS, (size_t)max_V * 4, st>>>(
+        scores, score_off, keep_k, kept_off, max_V, kept_idx, slot_of));
     return D3TOM_OK;
 }

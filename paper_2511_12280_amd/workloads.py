@@ -174,6 +174,7 @@ class SampleGen:
         # step-independent projections (float32, unrounded until the step is assembled)
         self._q_pv = np.concatenate([self.h_prompt, self.h_vis]) @ self.proj.wq
         self._k_pv = np.concatenate([self.h_prompt, self.h_vis]) @ self.proj.wk
+        self._qkv_pv = None
 
     def step(self, D: int) -> dict:
         """One denoising step: response = D decoded (decider) tokens followed by O-D mask slots."""
@@ -208,8 +209,11 @@ class SampleGen:
         nv = n_tokens - wl.P - wl.O
         if nv < 0 or nv > wl.V:
             raise ValueError("n_tokens out of range")
+        if self._qkv_pv is None:      # projections of prompt | all visual rows, computed once
+            self._qkv_pv = self.proj.qkv(np.concatenate([self.h_prompt, self.h_vis], axis=0))
         h_resp = np.concatenate([self.h_decoded[:D], np.repeat(self.h_mask, wl.O - D, axis=0)], axis=0)
-        return self.proj.qkv(np.concatenate([self.h_prompt, self.h_vis[:nv], h_resp], axis=0))
+        resp = self.proj.qkv(h_resp)
+        return tuple(np.concatenate([pv[:wl.P + nv], r], axis=0) for pv, r in zip(self._qkv_pv, resp))
 
 
 def random_case(seed: int, N: int, d: int, H: int, P: int, V: int, D: int, dtype: str = "f32",
