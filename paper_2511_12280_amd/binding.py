@@ -50,7 +50,7 @@ _lib.d3tom_importance.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _f, _vp, _vp, _
 _lib.d3tom_select_topk.restype = _i
 _lib.d3tom_select_topk.argtypes = [_vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_merge.restype = _i
-_lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i,
+_lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i,
                              _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
@@ -158,6 +158,7 @@ class Layout:
         self.Nm = [n - (v - k) for n, v, k in zip(self.N, self.V, self.keep)]
         self.max_N, self.max_V, self.max_keep = max(self.N), max(self.V), max(self.keep)
         self.min_D, self.max_D, self.max_Nm = min(self.D), max(self.D), max(self.Nm)
+        self.max_pruned = max(v - k for v, k in zip(self.V, self.keep))
         self.sum_N, self.sum_V, self.sum_keep, self.sum_Nm = sum(self.N), sum(self.V), sum(self.keep), sum(self.Nm)
 
         def pre(a):
@@ -212,7 +213,7 @@ def d3tom_merge(x: torch.Tensor, sim: Optional[torch.Tensor], lay: Layout, kept_
     d_sim = sim.shape[-1] if sim is not None else d
     _check(_lib.d3tom_merge(_ptr(x), _ptr(sim), d, d_sim, _dt(x), lay.B, _ptr(lay.seq_off), _ptr(lay.vis_start),
                             _ptr(lay.vis_count), _ptr(lay.vis_off), _ptr(kept_idx), _ptr(lay.kept_off),
-                            lay.max_N, lay.max_V, lay.max_keep, int(mode), _ptr(lay.out_off), _ptr(y),
+                            lay.max_N, lay.max_V, lay.max_keep, lay.max_pruned, int(mode), _ptr(lay.out_off), _ptr(y),
                             _ptr(assign), _ptr(counts), _ptr(src_pos), _ptr(ws), ws.numel(), _stream(stream)),
            "d3tom_merge")
     return y

@@ -21,7 +21,6 @@ namespace d3tom {
 
 constexpr int COS_BN = 128;        // kept slots per column tile
 constexpr int COS_BK = 64;         // contraction elements per LDS stage
-constexpr int COS_LDA = COS_BK + 8;   // padded LDS row length (elements)
 constexpr int FIN_THREADS = 1024;
 
 struct MergeWs {
@@ -136,23 +135,55 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 
 // ---- cosine GEMM + fused argmax, bf16 MFMA ---------------------------------------------------
 // Workgroup tile: (TM*64) pruned rows x 128 kept slots, 4 waves as 2 x 2, wave tile (TM*32) x 64.
+//
+// Operand tiles go HBM/L2 -> LDS with direct loads (global_load_lds, 16 bytes per lane, no register
+// staging) into a ring of COS_NS stages of 64 contraction elements; the loads of stage kt+3 are in
+// flight while stage kt feeds the MFMAs, one s_barrier per stage.  A wave-load writes 1 KB of LDS
+// contiguously (8 rows x 128 B), so rows cannot be padded; instead the 16-byte chunk that lands in
+// position p of row r is chunk p ^ ((r >> 1) & 7) of that row (the lane picks its global address
+// accordingly), which spreads the MFMA operand reads of 16 consecutive rows over all 64 banks.
+//
+// Workgroup ids are mapped to tiles per XCD: ids are dealt round-robin to the 8 XCDs, each XCD
+// owns a rectangular block of R x C tiles, so its private L2 only ever sees R row tiles and C column
+// tiles of the operands.
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+constexpr int COS_NS = 4;
+
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+    // N direct loads of this wave may stay in flight; everything older has landed in LDS
+    if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else {
+        static_assert(N == 0, "add the wait count");
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+}
+
 template <int TM>
 __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
-    float2* __restrict__ part) {
+    float2* __restrict__ part, int XC, int R, int C) {
     constexpr int BM = TM * 64;
-    constexpr int A_CH = BM * (COS_BK / 8) / 256;       // 16-byte chunks per thread, A tile
-    constexpr int B_CH = COS_BN * (COS_BK / 8) / 256;   // B tile
-    const int ct = blockIdx.x, rt = blockIdx.y, b = blockIdx.z;
-    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
-    if (rt * BM >= s.M || ct * COS_BN >= s.k) return;
-
-    __shared__ __attribute__((aligned(16))) uint16_t As[BM * COS_LDA];
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[COS_BN * COS_LDA];
+    constexpr int STAGE = (BM + COS_BN) * 128;          // bytes per ring stage (64 bf16 = 128 B per row)
+    constexpr int A_LD = BM / 32;                       // direct loads per wave and stage, A tile (8 rows each)
+    constexpr int B_LD = COS_BN / 32;
+    constexpr int LPS = A_LD + B_LD;                    // loads per wave and stage
+    extern __shared__ __attribute__((aligned(16))) char ring[];
     __shared__ float rnA[BM], rnB[COS_BN];
     __shared__ float2 red[2][BM];
+
+    const int per = 8 * R * C;
+    const int b = blockIdx.x / per;
+    const int rem = blockIdx.x % per, xcd = rem & 7, li = rem >> 3;
+    const int rt = (xcd / XC) * R + li / C, ct = (xcd % XC) * C + li % C;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    if (rt * BM >= s.M || ct * COS_BN >= s.k) return;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int wm = wave >> 1, wn = wave & 1;
@@ -162,28 +193,41 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const float* rn = rnorm + (size_t)b * max_V;
     const size_t base = (size_t)(s.tok0 + s.vs) * d;
 
-    // per-thread source rows of the global -> LDS copy (rows past the end re-read row 0; masked later)
-    const uint16_t* a_src[A_CH];
-    const uint16_t* b_src[B_CH];
+    // source address of this lane for each of its direct loads (rows past the end re-read row 0; masked later)
+    const uint16_t* a_src[A_LD];
+    const uint16_t* b_src[B_LD];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
+    for (int i = 0; i < A_LD; ++i) {
+        const int row = wave * (BM / 4) + i * 8 + (lane >> 3);
+        const int cg = (lane & 7) ^ ((row >> 1) & 7);
         const int p = rt * BM + row;
         const int m = (p < s.M) ? pr[p] : pr[0];
-        a_src[i] = f + base + (size_t)m * d + cc * 8;
+        a_src[i] = f + base + (size_t)m * d + cg * 8;
     }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
+    for (int i = 0; i < B_LD; ++i) {
+        const int row = wave * (COS_BN / 4) + i * 8 + (lane >> 3);
+        const int cg = (lane & 7) ^ ((row >> 1) & 7);
         const int r = ct * COS_BN + row;
         const int j = min(max(kp[(r < s.k) ? r : 0], 0), s.V - 1);
-        b_src[i] = f + base + (size_t)j * d + cc * 8;
+        b_src[i] = f + base + (size_t)j * d + cg * 8;
     }
     for (int t = tid; t < BM; t += 256) { const int p = rt * BM + t; rnA[t] = (p < s.M) ? rn[pr[p]] : 0.f; }
     for (int t = tid; t < COS_BN; t += 256) {
         const int r = ct * COS_BN + t;
         rnB[t] = (r < s.k) ? rn[min(max(kp[r], 0), s.V - 1)] : 0.f;
     }
+    auto issue = [&](int kt, int stage) {
+        char* sb = ring + stage * STAGE;
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_src[i] + kt * COS_BK),
+                                             (lds_ptr_t)(sb + (wave * (BM / 4) + i * 8) * 128), 16, 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+            __builtin_amdgcn_global_load_lds((glb_ptr_t)(b_src[i] + kt * COS_BK),
+                                             (lds_ptr_t)(sb + BM * 128 + (wave * (COS_BN / 4) + i * 8) * 128), 16, 0, 0);
+    };
 
     f32x16 acc[TM][2];
 #pragma unroll
@@ -193,42 +237,31 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-    uint4 a_reg[A_CH], b_reg[B_CH];
+    // byte offsets of this lane's operand fragments inside a stage (k-step kk adds the swizzled chunk)
+    int a_row[TM], b_row[2], a_sw[TM], b_sw[2];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4*>(a_src[i]);
+    for (int i = 0; i < TM; ++i) { const int Rr = wm * (TM * 32) + i * 32 + c; a_row[i] = Rr * 128; a_sw[i] = (Rr >> 1) & 7; }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const uint4*>(b_src[i]);
+    for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
 
     const int nkt = d / COS_BK;
+#pragma unroll
+    for (int st = 0; st < COS_NS - 1; ++st)
+        if (st < nkt) issue(st, st);
     for (int kt = 0; kt < nkt; ++kt) {
-        __syncthreads();                                   // previous stage fully consumed
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
-            *reinterpret_cast<uint4*>(&As[row * COS_LDA + cc * 8]) = a_reg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
-            const int ch = tid + 256 * i, row = ch >> 3, cc = ch & 7;
-            *reinterpret_cast<uint4*>(&Bs[row * COS_LDA + cc * 8]) = b_reg[i];
-        }
-        __syncthreads();
-        if (kt + 1 < nkt) {
-            const int ko = (kt + 1) * COS_BK;
-#pragma unroll
-            for (int i = 0; i < A_CH; ++i) a_reg[i] = *reinterpret_cast<const uint4*>(a_src[i] + ko);
-#pragma unroll
-            for (int i = 0; i < B_CH; ++i) b_reg[i] = *reinterpret_cast<const uint4*>(b_src[i] + ko);
-        }
+        if (kt + COS_NS - 2 < nkt) wait_loads_and_barrier<(COS_NS - 2) * LPS>();
+        else wait_loads_and_barrier<0>();
+        if (kt + COS_NS - 1 < nkt) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
+        const char* sb = ring + (kt % COS_NS) * STAGE;
 #pragma unroll
         for (int kk = 0; kk < COS_BK / 16; ++kk) {
             bf16x8 af[TM], bfr[2];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(&As[(wm * (TM * 32) + i * 32 + c) * COS_LDA + kk * 16 + g * 8]);
+                af[i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(&Bs[(wn * 64 + j * 32 + c) * COS_LDA + kk * 16 + g * 8]);
+                bfr[j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -476,12 +509,13 @@ using namespace d3tom;
 extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
                            int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
                            const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
-                           int max_N, int max_V, int max_keep, int mode,
+                           int max_N, int max_V, int max_keep, int max_pruned, int mode,
                            const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
                            void* ws, size_t ws_bytes, void* stream) {
     if (!x || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off || !y)
         return D3TOM_ERR_INVALID_ARG;
-    if (B < 1 || d < 1 || max_N < 1 || max_V < 1 || max_V > max_N || max_keep < 1 || max_keep > max_V)
+    if (B < 1 || d < 1 || max_N < 1 || max_V < 1 || max_V > max_N || max_keep < 1 || max_keep > max_V ||
+        max_pruned < 0 || max_pruned > max_V)
         return D3TOM_ERR_INVALID_ARG;
     if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
     if (mode != D3TOM_MERGE_MEAN && mode != D3TOM_MERGE_SUM) return D3TOM_ERR_INVALID_ARG;
@@ -508,7 +542,11 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
         if (hipFuncSetAttribute((const void*)merge_prep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 D3TOM_MAX_VISUAL * 4) != hipSuccess ||
             hipFuncSetAttribute((const void*)merge_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (2 * D3TOM_MAX_VISUAL + 1) * 4) != hipSuccess)
+                                (2 * D3TOM_MAX_VISUAL + 1) * 4) != hipSuccess ||
+            hipFuncSetAttribute((const void*)cos_argmax_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                COS_NS * (64 + COS_BN) * 128) != hipSuccess ||
+            hipFuncSetAttribute((const void*)cos_argmax_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                COS_NS * (128 + COS_BN) * 128) != hipSuccess)
             return D3TOM_ERR_DEVICE;
         attr_set = true;
     }
@@ -527,18 +565,27 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
     if (mfma) {
         const int nct = ceil_div(max_keep, COS_BN);
         // 128-row tiles unless that leaves most of the 256 CUs idle
-        const bool small = (long)nct * ceil_div(max_V, 128) * B < 384;
-        if (small) {
-            const dim3 g(nct, ceil_div(max_V, 64), B);
-            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 256, 0, st>>>(
-                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part));
-        } else {
-            const dim3 g(nct, ceil_div(max_V, 128), B);
-            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 256, 0, st>>>(
-                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part));
+        const int TM = ((long)nct * ceil_div(max_pruned, 128) * B >= 192) ? 2 : 1;
+        const int BM = TM * 64;
+        const int nrt = ceil_div(max_pruned > 0 ? max_pruned : 1, BM);
+        // XCD grid XR x XC (8 XCDs): fewest tiles per XCD first, then fewest operand rows per XCD
+        int XC = 1, R = ceil_div(nrt, 8), C = nct;
+        long best = -1;
+        for (int xc = 1; xc <= 8; xc <<= 1) {
+            const int xr = 8 / xc, r = ceil_div(nrt, xr), c = ceil_div(nct, xc);
+            const long cost = (long)r * c * 100000 + (long)r * BM + (long)c * COS_BN;
+            if (best < 0 || cost < best) { best = cost; XC = xc; R = r; C = c; }
         }
+        const dim3 g((unsigned)(8 * R * C * B));
+        const size_t lds = (size_t)COS_NS * (BM + COS_BN) * 128;
+        if (TM == 1)
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 256, lds, st>>>(
+                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, w.NCT, part, XC, R, C));
+        else
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 256, lds, st>>>(
+                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, w.NCT, part, XC, R, C));
     } else {
         const dim3 g(max_V, B);
         if (dt == D3TOM_BF16)
