@@ -103,12 +103,13 @@ def algorithmic(wl, lay):
     move / compute: K once per sweep, the visual rows once, input + output rows once, 4 n^2 d for attention)."""
     eb = 4 if wl.dtype == "f32" else 2
     d = wl.d
-    out = {k: [0.0, 0.0] for k in ("imp_stats", "imp_scores", "topk_select", "merge_prep", "merge_norms",
+    out = {k: [0.0, 0.0] for k in ("imp_stats", "imp_scores", "imp_finish", "topk_select", "merge_prep", "merge_norms",
                                    "cos_argmax", "merge_finalize", "merge_scatter", "attend")}
     for N, V, k, D, Nm in zip(lay.N, lay.V, lay.keep, lay.D, lay.Nm):
         M = V - k
         out["imp_stats"][0] += (N + D) * d * eb;            out["imp_stats"][1] += 2.0 * D * N * d
         out["imp_scores"][0] += (V + D) * d * eb + 4 * V;   out["imp_scores"][1] += 2.0 * D * V * d
+        out["imp_finish"][0] += 4 * V * (wl.H + 1)
         out["topk_select"][0] += 4 * V + 4 * k + 4 * V
         out["merge_prep"][0] += 4 * k + 4 * M
         out["merge_norms"][0] += V * d * eb + 4 * V

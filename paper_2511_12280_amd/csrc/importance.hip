@@ -6,10 +6,9 @@
 // decider rows are ever evaluated, in two sweeps over K:
 //
 //   sweep 1 (stats)   per (head, decider): running max and sum of exp2 over all keys, computed per
-//                     128-key chunk by one workgroup each and combined later in a fixed order
-//   sweep 2 (scores)  per (head, visual key): sum over deciders of exp2(logit - logsumexp); the
-//                     per-head partial rows are added in head order by whichever workgroup of a key
-//                     chunk finishes last (integer arrival counter, no float atomics)
+//                     256-key chunk by one workgroup each and combined later in a fixed order
+//   sweep 2 (scores)  per (head, visual key): sum over deciders of exp2(logit - logsumexp), one row
+//                     per head; a small third kernel adds the H rows in head order (no atomics)
 //
 // bf16 path: logits on MFMA 16x16x32 (rows = 16 deciders, cols = 16 keys, contraction = dh), both
 // operands read straight from HBM/L2 in the MFMA operand layout (each lane reads dh/4 contiguous
@@ -22,7 +21,7 @@
 
 namespace d3tom {
 
-constexpr int IMP_KC = 128;                    // keys per workgroup (4 waves x SUB sub-tiles x 16)
+constexpr int IMP_KC = 256;                    // keys per workgroup (4 waves x SUB sub-tiles x 16)
 constexpr int IMP_SUB = IMP_KC / (4 * 16);
 
 struct ImpWs {
@@ -60,19 +59,20 @@ __device__ __forceinline__ void load_frag(const uint16_t* row, int g, bool valid
     }
 }
 
+constexpr int IMP_NB = 4;       // 16-decider blocks whose query fragments are fetched together
+
+// (running max, running sum of exp2) of decider rows over one 128-key chunk of one head
 template <int DH>
 __global__ __launch_bounds__(256) void imp_stats_bf16(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
-    int max_D, int DPAD, int NCH, float2* __restrict__ part, int* __restrict__ counters, int NCHV) {
+    int max_D, int DPAD, int NCH, float2* __restrict__ part) {
     constexpr int KS = DH / 32;
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
     const int N = seq_off[b + 1] - tok0;
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
-    if (chunk == 0 && h == 0)
-        for (int t = threadIdx.x; t < NCHV; t += 256) counters[b * NCHV + t] = 0;
     const int key_base = chunk * IMP_KC;
     if (key_base >= N || D <= 0) return;
 
@@ -89,42 +89,48 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
         load_frag<DH>(row, g, kvalid[s], kf[s]);
     }
     const int nblk = (D + 15) >> 4;
-    for (int db = 0; db < nblk; ++db) {
-        const int i = db * 16 + r;
-        const bool qv = i < D;
-        int pos = qv ? dec[i] : 0;
-        pos = min(max(pos, 0), N - 1);
-        bf16x8 qf[KS];
-        load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf);
-        float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-        float z[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int db0 = 0; db0 < nblk; db0 += IMP_NB) {
+        bf16x8 qf[IMP_NB][KS];
 #pragma unroll
-        for (int s = 0; s < IMP_SUB; ++s) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int nb = 0; nb < IMP_NB; ++nb) {
+            const int i = (db0 + nb) * 16 + r;
+            const bool qv = i < D;
+            const int pos = min(max(qv ? dec[i] : 0, 0), N - 1);
+            load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf[nb]);
+        }
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[kk], kf[s][kk], acc, 0, 0, 0);
-            // acc[e]: decider row db*16 + 4g + e, key column r of sub-tile s
-            if (kvalid[s]) {
+        for (int nb = 0; nb < IMP_NB; ++nb) {
+            if (db0 + nb >= nblk) break;
+            float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            float z[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float l2 = acc[e] * scale2;
-                    const float mn = fmaxf(m[e], l2);
-                    z[e] = z[e] * exp2f(m[e] - mn) + exp2f(l2 - mn);
-                    m[e] = mn;
+            for (int s = 0; s < IMP_SUB; ++s) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < KS; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[nb][kk], kf[s][kk], acc, 0, 0, 0);
+                // acc[e]: decider row (db0+nb)*16 + 4g + e, key column r of sub-tile s
+                if (kvalid[s]) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float l2 = acc[e] * scale2;
+                        const float mn = fmaxf(m[e], l2);
+                        z[e] = z[e] * exp2f(m[e] - mn) + exp2f(l2 - mn);
+                        m[e] = mn;
+                    }
                 }
             }
-        }
-        // combine over the 16 key columns (lanes with equal g)
+            // combine over the 16 key columns (lanes with equal g): max first, then one rescale
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
+            for (int e = 0; e < 4; ++e) {
+                float mx = m[e];
 #pragma unroll
-            for (int o = 1; o < 16; o <<= 1) {
-                const float m2 = __shfl_xor(m[e], o, WAVE);
-                const float z2 = __shfl_xor(z[e], o, WAVE);
-                lse2_combine(m[e], z[e], m2, z2);
+                for (int o = 1; o < 16; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+                float zz = (m[e] == -INFINITY) ? 0.f : z[e] * exp2f(m[e] - mx);
+#pragma unroll
+                for (int o = 1; o < 16; o <<= 1) zz += __shfl_xor(zz, o, WAVE);
+                if (r == 0) wstat[wave][(db0 + nb) * 16 + 4 * g + e] = make_float2(mx, zz);
             }
-            if (r == 0) wstat[wave][db * 16 + 4 * g + e] = make_float2(m[e], z[e]);
         }
     }
     __syncthreads();
@@ -136,40 +142,26 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
     }
 }
 
+// per-head score rows: sp[h][j] = sum over deciders of exp2(logit - log2sumexp2)
 template <int DH>
 __global__ __launch_bounds__(256) void imp_scores_bf16(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
-    const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count, const int32_t* __restrict__ score_off,
-    int max_D, int max_V, int DPAD, int NCH, int NCHV, int VPAD,
-    const float2* __restrict__ part, float* __restrict__ sp, int* __restrict__ counters, float* __restrict__ scores) {
+    const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
+    int max_D, int max_V, int DPAD, int NCH, int VPAD, const float2* __restrict__ part, float* __restrict__ sp) {
     constexpr int KS = DH / 32;
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
     const int N = seq_off[b + 1] - tok0;
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
-    int vs = min(max(vis_start[b], 0), N);
+    const int vs = min(max(vis_start[b], 0), N);
     const int V = min(min(vis_count[b], max_V), N - vs);
     const int key_base = chunk * IMP_KC;
     if (key_base >= V || D <= 0) return;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
     __shared__ float c_lds[D3TOM_MAX_DECIDERS];
-    __shared__ int s_last;
-
-    // log2-sum-exp2 of every decider row of this head, chunks combined in ascending order
-    const int nch = (N + IMP_KC - 1) / IMP_KC;
-    for (int t = threadIdx.x; t < D; t += 256) {
-        const float2* p = part + ((size_t)(b * H + h) * NCH) * DPAD + t;
-        float m = -INFINITY, z = 0.f;
-        for (int c = 0; c < nch; ++c) {
-            const float2 a = p[(size_t)c * DPAD];
-            lse2_combine(m, z, a.x, a.y);
-        }
-        c_lds[t] = m + log2f(z);
-    }
-    __syncthreads();
 
     bf16x8 kf[IMP_SUB][KS];
     float acc_s[IMP_SUB];
@@ -181,28 +173,50 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
         load_frag<DH>(row, g, kv, kf[s]);
         acc_s[s] = 0.f;
     }
-    const int nblk = (D + 15) >> 4;
-    for (int db = 0; db < nblk; ++db) {
-        const int i = db * 16 + r;
-        const bool qv = i < D;
-        int pos = qv ? dec[i] : 0;
-        pos = min(max(pos, 0), N - 1);
-        bf16x8 qf[KS];
-        load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf);
-        float cc[4];
+    // log2-sum-exp2 of every decider row of this head, key chunks combined in ascending order
+    const int nch = (N + IMP_KC - 1) / IMP_KC;
+    for (int t = threadIdx.x; t < D; t += 256) {
+        const float2* p = part + ((size_t)(b * H + h) * NCH) * DPAD + t;
+        float m = -INFINITY, z = 0.f;
+        for (int c0 = 0; c0 < nch; c0 += 8) {              // 8 independent loads in flight, combined in order
+            float2 a[8];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const int row = db * 16 + 4 * g + e;
-            cc[e] = (row < D) ? c_lds[row] : INFINITY;          // padded rows contribute exp2(-inf) = 0
+            for (int u = 0; u < 8; ++u) a[u] = (c0 + u < nch) ? p[(size_t)(c0 + u) * DPAD] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) lse2_combine(m, z, a[u].x, a[u].y);
+        }
+        c_lds[t] = m + log2f(z);
+    }
+    __syncthreads();
+
+    const int nblk = (D + 15) >> 4;
+    for (int db0 = 0; db0 < nblk; db0 += IMP_NB) {
+        bf16x8 qf[IMP_NB][KS];
+#pragma unroll
+        for (int nb = 0; nb < IMP_NB; ++nb) {
+            const int i = (db0 + nb) * 16 + r;
+            const bool qv = i < D;
+            const int pos = min(max(qv ? dec[i] : 0, 0), N - 1);
+            load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf[nb]);
         }
 #pragma unroll
-        for (int s = 0; s < IMP_SUB; ++s) {
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int nb = 0; nb < IMP_NB; ++nb) {
+            if (db0 + nb >= nblk) break;
+            float cc[4];
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[kk], kf[s][kk], acc, 0, 0, 0);
+            for (int e = 0; e < 4; ++e) {
+                const int row = (db0 + nb) * 16 + 4 * g + e;
+                cc[e] = (row < D) ? c_lds[row] : INFINITY;       // padded rows contribute exp2(-inf) = 0
+            }
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc_s[s] += exp2f(acc[e] * scale2 - cc[e]);
+            for (int s = 0; s < IMP_SUB; ++s) {
+                f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int kk = 0; kk < KS; ++kk)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[nb][kk], kf[s][kk], acc, 0, 0, 0);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) acc_s[s] += exp2f(acc[e] * scale2 - cc[e]);
+            }
         }
     }
     float* sp_row = sp + (size_t)(b * H + h) * VPAD;
@@ -213,23 +227,27 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
         v += __shfl_xor(v, 32, WAVE);
         if (g == 0) sp_row[key_base + (wave * IMP_SUB + s) * 16 + r] = v;
     }
-    // arrival counter: the last head to finish this key chunk adds the H partial rows in head order
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) s_last = (atomicAdd(&counters[b * NCHV + chunk], 1) == H - 1);
-    __syncthreads();
-    if (!s_last) return;
-    __threadfence();
-    const float invH = 1.0f / (float)H;
-    for (int t = threadIdx.x; t < IMP_KC; t += 256) {
-        const int j = key_base + t;
-        if (j < V) {
-            float s = 0.f;
-            for (int hh = 0; hh < H; ++hh)
-                s += __builtin_nontemporal_load(sp + (size_t)(b * H + hh) * VPAD + j);
-            scores[score_off[b] + j] = s * invH;
-        }
+}
+
+// S_j = mean over heads of the per-head rows, heads added in ascending order
+__global__ __launch_bounds__(256) void imp_finish_kernel(
+    const float* __restrict__ sp, int H, int VPAD, const int32_t* __restrict__ seq_off,
+    const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count, const int32_t* __restrict__ score_off,
+    int max_V, float* __restrict__ scores) {
+    const int b = blockIdx.y, j = blockIdx.x * 256 + threadIdx.x;
+    const int N = seq_off[b + 1] - seq_off[b];
+    const int vs = min(max(vis_start[b], 0), N);
+    const int V = min(min(vis_count[b], max_V), N - vs);
+    if (j >= V) return;
+    float s = 0.f;
+    for (int h0 = 0; h0 < H; h0 += 8) {                    // 8 independent loads in flight, added in head order
+        float a[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) a[u] = (h0 + u < H) ? sp[(size_t)(b * H + h0 + u) * VPAD + j] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) s += a[u];
     }
+    scores[score_off[b] + j] = s / (float)H;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -328,23 +346,24 @@ extern "C" int d3tom_importance(const void* q, const void* k, int dt,
     if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
         float2* part = (float2*)(wsb + w.part_off);
         float* sp = (float*)(wsb + w.sp_off);
-        int* cnt = (int*)(wsb + w.cnt_off);
-        const dim3 g1(w.NCH, H, B), g2(w.NCHV, H, B);
+        const dim3 g1(w.NCH, H, B), g2(w.NCHV, H, B), g3(ceil_div(max_V, 256), B);
         const uint16_t* qq = (const uint16_t*)q;
         const uint16_t* kk = (const uint16_t*)k;
         if (dh == 128) {
             D3TOM_LAUNCH(IMP_STATS, st, imp_stats_bf16<128><<<g1, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV));
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part));
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<128><<<g2, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
-                w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores));
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.VPAD,
+                part, sp));
         } else {
             D3TOM_LAUNCH(IMP_STATS, st, imp_stats_bf16<64><<<g1, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, cnt, w.NCHV));
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part));
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<64><<<g2, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD,
-                w.NCH, w.NCHV, w.VPAD, part, sp, cnt, scores));
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.VPAD,
+                part, sp));
         }
+        D3TOM_LAUNCH(IMP_FINISH, st, imp_finish_kernel<<<g3, 256, 0, st>>>(
+            sp, H, w.VPAD, seq_off, vis_start, vis_count, score_off, max_V, scores));
         return D3TOM_OK;
     }
     float* cws = (float*)(wsb + w.c_off);

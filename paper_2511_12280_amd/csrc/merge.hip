@@ -565,7 +565,7 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
     if (mfma) {
         const int nct = ceil_div(max_keep, COS_BN);
         // 128-row tiles unless that leaves most of the 256 CUs idle
-        const int TM = ((long)nct * ceil_div(max_pruned, 128) * B >= 192) ? 2 : 1;
+        const int TM = ((long)nct * ceil_div(max_pruned, 128) * B >= 96) ? 2 : 1;
         const int BM = TM * 64;
         const int nrt = ceil_div(max_pruned > 0 ? max_pruned : 1, BM);
         // XCD grid XR x XC (8 XCDs): fewest tiles per XCD first, then fewest operand rows per XCD
