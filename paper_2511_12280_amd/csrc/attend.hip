@@ -5,15 +5,19 @@
 // inside one lane:
 //     S^T = K Q^T      A = K tile (LDS, row-major), B = Q^T (registers, loaded once per workgroup)
 //     P^T = exp2(S^T * scale*log2e - m)            in registers, the MFMA accumulator layout
-//     O^T += V^T P^T   A = V^T tile (LDS, transposed while it is stored), B = P^T straight from the
-//                      accumulator registers of the first product (no LDS round trip for P)
+//     O^T += V^T P^T   A = V^T, read from the row-major V tile in LDS with the transposing LDS read
+//                      (ds_read_b64_tr_b16), B = P^T straight from the accumulator registers of the
+//                      first product (no LDS round trip for P)
 // In the accumulator layout a lane owns ONE query column (lane % 32) and 16 of the 32 key rows, so
 // the running max / sum of the online softmax need one cross-lane exchange (lane ^ 32) per tile and
 // the rescale of O^T is a per-lane scalar.  The contraction index of the second product (keys) is
 // fed in the order the accumulator holds it; V^T is read from LDS in that same order.
 //
-// Workgroup = 4 waves x 32 queries of one head, 64 keys per LDS stage, global loads of the next
-// stage overlap the MFMAs of the current one.  Softmax state and accumulators are float32.
+// Workgroup = 4 waves x 32 queries of one head, 64 keys per LDS stage.  K and V tiles go HBM/L2 -> LDS
+// with direct loads (global_load_lds, no register staging) into a two-stage ring, so the loads of the
+// next stage overlap the MFMAs of the current one and one s_barrier per stage suffices; rows are
+// unpadded and their 16-byte chunks XOR-swizzled by the row index instead.  Softmax state and
+// accumulators are float32; two workgroups fit a CU.
 //
 // The generic path (float32 or any head size) is one workgroup per (query, head) with a chunked
 // online softmax in plain float arithmetic.
@@ -23,26 +27,47 @@ namespace d3tom {
 
 constexpr int ATT_BQ = 128;     // queries per workgroup
 constexpr int ATT_BK = 64;      // keys per stage
+constexpr int ATT_NS = 2;       // LDS ring depth
+
+typedef __attribute__((address_space(3))) void* att_lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* att_glb_ptr_t;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short att_short4;
+
+// 4 keys x 16 dims of a row-major LDS tile, transposed on the way to the registers: within each group
+// of 16 lanes, lanes 4j..4j+3 point at 4 x 4 consecutive elements of row j, and lane i receives
+// column i of that 4 x 16 block (ds_read_b64_tr_b16).
+__device__ __forceinline__ att_short4 lds_read_tr16(const char* p) {
+    typedef __attribute__((address_space(3))) att_short4* lp;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p);
+}
+
+template <int N>
+__device__ __forceinline__ void att_wait_and_barrier() {
+    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else {
+        static_assert(N == 8, "add the wait count");
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    }
+}
 
 template <int DH>
-__global__ __launch_bounds__(256) void attend_bf16_kernel(
+__global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu, int H, float scale2, uint16_t* __restrict__ o) {
-    constexpr int KS = DH / 16;            // k-steps of the first product
-    constexpr int DT = DH / 32;            // 32-dim tiles of O^T
-    constexpr int K_LD = DH + 8;           // padded K row (elements)
-    constexpr int V_LD = ATT_BK + 8;       // padded V^T row (elements)
-    constexpr int K_CH = ATT_BK * (DH / 8) / 256;           // 16-byte chunks per thread, K tile
-    constexpr int V_BLK = (ATT_BK / 4) * (DH / 8);          // 4-key x 8-dim blocks in a V tile
-    constexpr int V_PT = (V_BLK + 255) / 256;
+    constexpr int KS = DH / 16;                 // k-steps of the first product
+    constexpr int DT = DH / 32;                 // 32-dim tiles of O^T
+    constexpr int ROWB = DH * 2;                // bytes per K / V row in LDS (unpadded, chunks swizzled)
+    constexpr int NCHK = DH / 8;                // 16-byte chunks per row
+    constexpr int RPI = 64 / NCHK;              // rows covered by one wave-wide direct load (1 KB)
+    constexpr int LD = ATT_BK / (4 * RPI);      // direct loads per wave, per operand, per stage
+    constexpr int TILE = ATT_BK * ROWB;         // bytes of one K (or V) tile
+    constexpr int STAGE = 2 * TILE;
+    extern __shared__ __attribute__((aligned(16))) char ring[];
 
     const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = cu[b];
     const int n = cu[b + 1] - tok0;
     if (qt * ATT_BQ >= n) return;
-
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[ATT_BK * K_LD];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[DH * V_LD];
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int c = lane & 31, g = lane >> 5;
@@ -67,66 +92,37 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(
     for (int t = 0; t < DT; ++t)
 #pragma unroll
         for (int e = 0; e < 16; ++e) ot[t][e] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;       // running max of the RAW logits, running sum of exp2
 
-    uint4 k_reg[K_CH], v_reg[V_PT][4];
-    auto load_tile = [&](int key0) {
+    // direct loads: lane -> (row, chunk position); the chunk fetched into position p of row r is
+    // p ^ (r & 15) for K (operand reads walk 16+ consecutive rows) and p ^ ((r & 3) * 4) for V
+    // (transposing reads touch 4 consecutive rows per 16-lane group)
+    const int ld_row = wave * (ATT_BK / 4) + lane / NCHK;       // + i * RPI
+    const int ld_pos = lane % NCHK;
+    auto issue = [&](int key0, int stage) {
+        char* sb = ring + stage * STAGE;
 #pragma unroll
-        for (int i = 0; i < K_CH; ++i) {
-            const int ch = tid + 256 * i, row = ch / (DH / 8), cc = ch % (DH / 8);
-            const int key = key0 + row;
-            k_reg[i] = (key < n) ? *reinterpret_cast<const uint4*>(kb + (size_t)key * rs + cc * 8) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < V_PT; ++i) {
-            const int blk = tid + 256 * i;
-            if (blk < V_BLK) {
-                const int kg = blk / (DH / 8), dg = blk % (DH / 8);
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const int key = key0 + kg * 4 + jj;
-                    v_reg[i][jj] = (key < n) ? *reinterpret_cast<const uint4*>(vb + (size_t)key * rs + dg * 8) : make_uint4(0, 0, 0, 0);
-                }
-            }
+        for (int i = 0; i < LD; ++i) {
+            const int r = ld_row + i * RPI;
+            const int key = min(key0 + r, n - 1);                // rows past the end re-read the last key (masked)
+            const int kc = (ld_pos ^ (r & 15)) & (NCHK - 1);
+            const int vc = (ld_pos ^ ((r & 3) * 4)) & (NCHK - 1);
+            __builtin_amdgcn_global_load_lds((att_glb_ptr_t)(kb + (size_t)key * rs + kc * 8),
+                                             (att_lds_ptr_t)(sb + (wave * (ATT_BK / 4) + i * RPI) * ROWB), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((att_glb_ptr_t)(vb + (size_t)key * rs + vc * 8),
+                                             (att_lds_ptr_t)(sb + TILE + (wave * (ATT_BK / 4) + i * RPI) * ROWB), 16, 0, 0);
         }
     };
-    auto store_tile = [&]() {
-#pragma unroll
-        for (int i = 0; i < K_CH; ++i) {
-            const int ch = tid + 256 * i, row = ch / (DH / 8), cc = ch % (DH / 8);
-            *reinterpret_cast<uint4*>(&Ks[row * K_LD + cc * 8]) = k_reg[i];
-        }
-#pragma unroll
-        for (int i = 0; i < V_PT; ++i) {
-            const int blk = tid + 256 * i;
-            if (blk < V_BLK) {
-                const int kg = blk / (DH / 8), dg = blk % (DH / 8);
-                const uint32_t w0[4] = {v_reg[i][0].x, v_reg[i][0].y, v_reg[i][0].z, v_reg[i][0].w};
-                const uint32_t w1[4] = {v_reg[i][1].x, v_reg[i][1].y, v_reg[i][1].z, v_reg[i][1].w};
-                const uint32_t w2[4] = {v_reg[i][2].x, v_reg[i][2].y, v_reg[i][2].z, v_reg[i][2].w};
-                const uint32_t w3[4] = {v_reg[i][3].x, v_reg[i][3].y, v_reg[i][3].z, v_reg[i][3].w};
-#pragma unroll
-                for (int p = 0; p < 4; ++p) {               // dims 8dg + 2p, 8dg + 2p + 1
-                    uint2 lo, hi;
-                    lo.x = (w0[p] & 0xFFFFu) | (w1[p] << 16);
-                    lo.y = (w2[p] & 0xFFFFu) | (w3[p] << 16);
-                    hi.x = (w0[p] >> 16) | (w1[p] & 0xFFFF0000u);
-                    hi.y = (w2[p] >> 16) | (w3[p] & 0xFFFF0000u);
-                    *reinterpret_cast<uint2*>(&Vt[(dg * 8 + 2 * p) * V_LD + kg * 4]) = lo;
-                    *reinterpret_cast<uint2*>(&Vt[(dg * 8 + 2 * p + 1) * V_LD + kg * 4]) = hi;
-                }
-            }
-        }
-    };
+    // transposing-read geometry of this lane: 16-lane group -> (g, dim half), lane in group -> (row j, 4-dim quad t)
+    const int tr_j = (lane & 15) >> 2, tr_t = lane & 3, tr_half = (lane >> 4) & 1;
 
     const int ntile = (n + ATT_BK - 1) / ATT_BK;
-    load_tile(0);
+    issue(0, 0);
     for (int it = 0; it < ntile; ++it) {
         const int key0 = it * ATT_BK;
-        __syncthreads();                    // previous stage fully consumed
-        store_tile();
-        __syncthreads();
-        if (it + 1 < ntile) load_tile(key0 + ATT_BK);
+        att_wait_and_barrier<0>();                             // stage `it` has landed; stage it-1 is free
+        if (it + 1 < ntile) issue(key0 + ATT_BK, (it + 1) % ATT_NS);
+        const char* sb = ring + (it % ATT_NS) * STAGE;
 
         // S^T = K Q^T for two 32-key tiles
         f32x16 st[2];
@@ -134,43 +130,54 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(
         for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) st[kt][e] = 0.f;
+            const int r = kt * 32 + c;
+            const char* krow = sb + r * ROWB;
 #pragma unroll
             for (int kk = 0; kk < KS; ++kk) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8*>(&Ks[(kt * 32 + c) * K_LD + kk * 16 + g * 8]);
+                const bf16x8 af = *reinterpret_cast<const bf16x8*>(krow + ((((kk * 2 + g) ^ (r & 15)) & (NCHK - 1)) << 4));
                 st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[kk], st[kt], 0, 0, 0);
             }
         }
-        // online softmax (base 2); element e of st[kt]: key kt*32 + (e/4)*8 + 4g + e%4, query c
-        float tmax = -INFINITY;
+        // online softmax in base 2 on the raw logits; element e of st[kt]: key kt*32 + (e/4)*8 + 4g + e%4, query c
+        if (key0 + ATT_BK > n) {
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = key0 + kt * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                    if (key >= n) st[kt][e] = -INFINITY;
+                }
+        }
+        float tmax = st[0][0];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int key = key0 + kt * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                const float s2 = (key < n) ? st[kt][e] * scale2 : -INFINITY;
-                st[kt][e] = s2;
-                tmax = fmaxf(tmax, s2);
-            }
+            for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, st[kt][e]);
         tmax = fmaxf(tmax, __shfl_xor(tmax, 32, WAVE));
         const float m_new = fmaxf(m_run, tmax);            // finite: every stage holds >= 1 valid key
-        const float alpha = exp2f(m_run - m_new);
+        const float ms = m_new * scale2;
         float psum = 0.f;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = exp2f(st[kt][e] - m_new);
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[kt][e], scale2, -ms));
                 st[kt][e] = p;
                 psum += p;
             }
         psum += __shfl_xor(psum, 32, WAVE);
-        l_run = l_run * alpha + psum;
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {      // some query of this wave moved its max
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+            l_run *= alpha;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
+        }
+        l_run += psum;
         m_run = m_new;
-#pragma unroll
-        for (int t = 0; t < DT; ++t)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
         // O^T += V^T P^T
+        const char* vt = sb + TILE;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -178,14 +185,21 @@ __global__ __launch_bounds__(256) void attend_bf16_kernel(
                 bf16x8 pf;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) pf[j] = (__bf16)st[kt][hh * 8 + j];
-                const int kofs = kt * 32 + hh * 16 + g * 4;          // keys kofs..+3 and kofs+8..+11
+                // k-slots j = 0..3 of lane (., g): keys kofs + j; j = 4..7: keys kofs + 8 + (j - 4)
+                const int key_a = kt * 32 + hh * 16 + g * 4 + tr_j;
+                const int key_b = key_a + 8;
+                const char* ra = vt + key_a * ROWB + tr_t % 2 * 8;
+                const char* rb = vt + key_b * ROWB + tr_t % 2 * 8;
+                const int sw_a = (key_a & 3) * 4, sw_b = (key_b & 3) * 4;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
-                    const uint16_t* vr = &Vt[(t * 32 + c) * V_LD + kofs];
-                    const bf16x4 v0 = *reinterpret_cast<const bf16x4*>(vr);
-                    const bf16x4 v1 = *reinterpret_cast<const bf16x4*>(vr + 8);
-                    const bf16x8 vf = {v0[0], v0[1], v0[2], v0[3], v1[0], v1[1], v1[2], v1[3]};
-                    ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, ot[t], 0, 0, 0);
+                    const int chunk = t * 4 + tr_half * 2 + (tr_t >> 1);
+                    const att_short4 va = lds_read_tr16(ra + (((chunk ^ sw_a) & (NCHK - 1)) << 4));
+                    const att_short4 vb2 = lds_read_tr16(rb + (((chunk ^ sw_b) & (NCHK - 1)) << 4));
+                    union { short s[8]; bf16x8 b; } u;
+                    u.s[0] = va[0]; u.s[1] = va[1]; u.s[2] = va[2]; u.s[3] = va[3];
+                    u.s[4] = vb2[0]; u.s[5] = vb2[1]; u.s[6] = vb2[2]; u.s[7] = vb2[3];
+                    ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.b, pf, ot[t], 0, 0, 0);
                 }
             }
     }
@@ -270,11 +284,21 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
     const float scale2 = scale * LOG2E;
     if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
         const dim3 g(ceil_div(max_seqlen, ATT_BQ), H, B);
+        const size_t lds = (size_t)ATT_NS * 2 * ATT_BK * dh * 2;
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute((const void*)attend_bf16_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    ATT_NS * 2 * ATT_BK * 128 * 2) != hipSuccess ||
+                hipFuncSetAttribute((const void*)attend_bf16_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    ATT_NS * 2 * ATT_BK * 64 * 2) != hipSuccess)
+                return D3TOM_ERR_DEVICE;
+            attr_set = true;
+        }
         if (dh == 128)
-            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<128><<<g, 256, 0, st>>>(
+            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<128><<<g, 256, lds, st>>>(
                 (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, scale2, (uint16_t*)o));
         else
-            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<64><<<g, 256, 0, st>>>(
+            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<64><<<g, 256, lds, st>>>(
                 (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, scale2, (uint16_t*)o));
     } else {
         const dim3 g(max_seqlen, H, B);
