@@ -155,8 +155,8 @@ int d3tom_select_topk(const float* scores, int B, const int32_t* score_off, cons
  *   sim       NULL (use x) or [seq_off[B], d_sim] dt: rows the cosine is taken on
  *   d, d_sim  row lengths (d_sim ignored when sim is NULL)
  *   kept_idx, kept_off   as written by d3tom_select_topk
- *   max_N, max_V, max_keep, max_pruned  host-known maxima over the batch of N_b, |V_b|, keep_k[b]
- *             and |V_b| - keep_k[b]
+ *   max_N, max_V, max_keep, max_pruned, max_out  host-known maxima over the batch of N_b, |V_b|,
+ *             keep_k[b], |V_b| - keep_k[b] and the output row count N_b - (|V_b| - keep_k[b])
  *   out_off   int32[B+1]  first output row of each sample; sample b emits
  *             N_b - (vis_count[b] - keep_k[b]) rows (Section 3.2, the post-merge length)
  *   y         [out_off[B], d] dt  out
@@ -169,7 +169,7 @@ int d3tom_select_topk(const float* scores, int B, const int32_t* score_off, cons
 int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
                 int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
                 const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
-                int max_N, int max_V, int max_keep, int max_pruned, int mode,
+                int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
                 const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
                 void* ws, size_t ws_bytes, void* stream);
 

@@ -50,7 +50,7 @@ _lib.d3tom_importance.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _f, _vp, _vp, _
 _lib.d3tom_select_topk.restype = _i
 _lib.d3tom_select_topk.argtypes = [_vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_merge.restype = _i
-_lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i,
+_lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
                              _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
@@ -213,7 +213,7 @@ def d3tom_merge(x: torch.Tensor, sim: Optional[torch.Tensor], lay: Layout, kept_
     d_sim = sim.shape[-1] if sim is not None else d
     _check(_lib.d3tom_merge(_ptr(x), _ptr(sim), d, d_sim, _dt(x), lay.B, _ptr(lay.seq_off), _ptr(lay.vis_start),
                             _ptr(lay.vis_count), _ptr(lay.vis_off), _ptr(kept_idx), _ptr(lay.kept_off),
-                            lay.max_N, lay.max_V, lay.max_keep, lay.max_pruned, int(mode), _ptr(lay.out_off), _ptr(y),
+                            lay.max_N, lay.max_V, lay.max_keep, lay.max_pruned, lay.max_Nm, int(mode), _ptr(lay.out_off), _ptr(y),
                             _ptr(assign), _ptr(counts), _ptr(src_pos), _ptr(ws), ws.numel(), _stream(stream)),
            "d3tom_merge")
     return y

@@ -101,32 +101,30 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
 #pragma unroll
         for (int nb = 0; nb < IMP_NB; ++nb) {
             if (db0 + nb >= nblk) break;
-            float m[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-            float z[4] = {0.f, 0.f, 0.f, 0.f};
+            // l2[s][e]: scaled logit of decider row (db0+nb)*16 + 4g + e and key column r of sub-tile s
+            f32x4 l2[IMP_SUB];
 #pragma unroll
             for (int s = 0; s < IMP_SUB; ++s) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk)
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[nb][kk], kf[s][kk], acc, 0, 0, 0);
-                // acc[e]: decider row (db0+nb)*16 + 4g + e, key column r of sub-tile s
-                if (kvalid[s]) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float l2 = acc[e] * scale2;
-                        const float mn = fmaxf(m[e], l2);
-                        z[e] = z[e] * exp2f(m[e] - mn) + exp2f(l2 - mn);
-                        m[e] = mn;
-                    }
-                }
+                for (int e = 0; e < 4; ++e) l2[s][e] = kvalid[s] ? acc[e] * scale2 : -INFINITY;
             }
-            // combine over the 16 key columns (lanes with equal g): max first, then one rescale
+            // max over this wave's 64 keys first (in-lane, then the 16 key columns), then one exp2 per logit
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float mx = m[e];
+                float mx = l2[0][e];
+#pragma unroll
+                for (int s = 1; s < IMP_SUB; ++s) mx = fmaxf(mx, l2[s][e]);
 #pragma unroll
                 for (int o = 1; o < 16; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
-                float zz = (m[e] == -INFINITY) ? 0.f : z[e] * exp2f(m[e] - mx);
+                float zz = 0.f;
+                if (mx != -INFINITY) {
+#pragma unroll
+                    for (int s = 0; s < IMP_SUB; ++s) zz += __builtin_amdgcn_exp2f(l2[s][e] - mx);
+                }
 #pragma unroll
                 for (int o = 1; o < 16; o <<= 1) zz += __shfl_xor(zz, o, WAVE);
                 if (r == 0) wstat[wave][(db0 + nb) * 16 + 4 * g + e] = make_float2(mx, zz);
@@ -215,7 +213,7 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
                 for (int kk = 0; kk < KS; ++kk)
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[nb][kk], kf[s][kk], acc, 0, 0, 0);
 #pragma unroll
-                for (int e = 0; e < 4; ++e) acc_s[s] += exp2f(acc[e] * scale2 - cc[e]);
+                for (int e = 0; e < 4; ++e) acc_s[s] += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[e], scale2, -cc[e]));
             }
         }
     }

@@ -24,7 +24,7 @@ constexpr int COS_BK = 64;         // contraction elements per LDS stage
 constexpr int FIN_THREADS = 1024;
 
 struct MergeWs {
-    size_t pruned_off, rnorm_off, part_off, assign_off, seg_off, mem_off, total;
+    size_t pruned_off, rnorm_off, part_off, seg_off, mem_off, total;
     int NCT;
 };
 __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
@@ -34,7 +34,6 @@ __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
     w.pruned_off = o; o += align_up((size_t)B * max_V * 4, 256);
     w.rnorm_off = o;  o += align_up((size_t)B * max_V * 4, 256);
     w.part_off = o;   o += align_up((size_t)B * w.NCT * max_V * 8, 256);
-    w.assign_off = o; o += align_up((size_t)B * max_V * 4, 256);
     w.seg_off = o;    o += align_up((size_t)B * (max_V + 1) * 4, 256);
     w.mem_off = o;    o += align_up((size_t)B * max_V * 4, 256);
     w.total = o;
@@ -244,30 +243,39 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
     for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
 
+    // Rows are a power-of-two number of bytes apart, so one 128-byte k-slice of every row falls on the
+    // same memory channel.  Workgroups that run side by side on an XCD therefore start their sweep over
+    // the contraction index at staggered offsets (a dot product does not care where it starts).
     const int nkt = d / COS_BK;
+    const int rot = li % min(nkt, 16);
+    auto kslice = [&](int kt) { const int t = kt + rot; return t >= nkt ? t - nkt : t; };
 #pragma unroll
     for (int st = 0; st < COS_NS - 1; ++st)
-        if (st < nkt) issue(st, st);
+        if (st < nkt) issue(kslice(st), st);
     for (int kt = 0; kt < nkt; ++kt) {
         if (kt + COS_NS - 2 < nkt) wait_loads_and_barrier<(COS_NS - 2) * LPS>();
         else wait_loads_and_barrier<0>();
-        if (kt + COS_NS - 1 < nkt) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
+        if (kt + COS_NS - 1 < nkt) issue(kslice(kt + COS_NS - 1), (kt + COS_NS - 1) % COS_NS);
         const char* sb = ring + (kt % COS_NS) * STAGE;
+        // all operand fragments of the stage are requested up front; the MFMAs start as the first
+        // ones arrive and run under the remaining LDS reads
+        bf16x8 af[COS_BK / 16][TM], bfr[COS_BK / 16][2];
 #pragma unroll
         for (int kk = 0; kk < COS_BK / 16; ++kk) {
-            bf16x8 af[TM], bfr[2];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
+                af[kk][i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
+                bfr[kk][j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
+        }
+#pragma unroll
+        for (int kk = 0; kk < COS_BK / 16; ++kk)
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-        }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
     }
 
     // epilogue: cosine = dot * rn_row * rn_col; per row, best (value, slot) over this tile's columns
@@ -345,12 +353,16 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
 }
 
 // ---- finalize: argmax over column tiles, CSR of all visual tokens by slot -------------------
+// Every thread owns up to FIN_PER visual tokens of each kind (pruned list entry / kept slot) and keeps
+// their destination slot in registers between the histogram and the fill, so nothing is re-read from
+// global memory.  Members are packed (slot << 14 | token) while they sit in LDS.
+constexpr int FIN_PER = D3TOM_MAX_VISUAL / FIN_THREADS;     // 16
 __global__ __launch_bounds__(FIN_THREADS) void merge_finalize_kernel(
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
     const int32_t* __restrict__ vis_off, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float2* __restrict__ part, int NCT, int nct_used_per_128,
-    int32_t* __restrict__ assign_out, int32_t* __restrict__ assign_ws, int32_t* __restrict__ counts,
-    int32_t* __restrict__ seg_off, int32_t* __restrict__ members) {
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float2* __restrict__ part, int NCT, int tiled,
+    int32_t* __restrict__ assign_out, int32_t* __restrict__ counts, int32_t* __restrict__ seg_off,
+    int32_t* __restrict__ members) {
     extern __shared__ int lds[];      // off[max_keep + 1] | mem[max_V]
     __shared__ int wsum[17];
     const int b = blockIdx.x;
@@ -361,29 +373,42 @@ __global__ __launch_bounds__(FIN_THREADS) void merge_finalize_kernel(
     const int tid = threadIdx.x;
     const int32_t* pr = pruned + (size_t)b * max_V;
     const int32_t* kp = kept_idx + kept_off[b];
-    int32_t* asg = assign_ws + (size_t)b * max_V;
     int32_t* asg_out = assign_out ? assign_out + vis_off[b] : nullptr;
-    const int nct = nct_used_per_128 ? (s.k + COS_BN - 1) / COS_BN : 1;
+    const int nct = tiled ? (s.k + COS_BN - 1) / COS_BN : 1;
+    const float2* pb = part + (size_t)b * NCT * max_V;
 
     for (int r = tid; r <= s.k; r += FIN_THREADS) off[r] = 0;
     __syncthreads();
-    for (int p = tid; p < s.M; p += FIN_THREADS) {
-        float bv = -INFINITY; int bi = 0;
-        for (int ct = 0; ct < nct; ++ct) {
-            const float2 a = part[((size_t)b * NCT + ct) * max_V + p];
-            if (a.x > bv) { bv = a.x; bi = __float_as_int(a.y); }
+    int tok[FIN_PER], slot[FIN_PER];                   // pruned tokens of this thread and where they go
+#pragma unroll
+    for (int u = 0; u < FIN_PER; ++u) {
+        const int p = tid + u * FIN_THREADS;
+        tok[u] = -1; slot[u] = 0;
+        if (p < s.M) {
+            float bv = -INFINITY; int bi = 0;
+            for (int c0 = 0; c0 < nct; c0 += 4) {          // 4 independent loads in flight; ascending tiles,
+                float2 a[4];                                // strict '>' keeps the lowest slot on ties
+#pragma unroll
+                for (int w = 0; w < 4; ++w) a[w] = (c0 + w < nct) ? pb[(size_t)(c0 + w) * max_V + p] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+                for (int w = 0; w < 4; ++w) if (a[w].x > bv) { bv = a[w].x; bi = __float_as_int(a[w].y); }
+            }
+            bi = min(max(bi, 0), s.k - 1);
+            tok[u] = pr[p]; slot[u] = bi;
+            if (asg_out) asg_out[tok[u]] = bi;
+            atomicAdd(&off[bi], 1);
         }
-        bi = min(max(bi, 0), s.k - 1);
-        const int m = pr[p];
-        asg[m] = bi;
-        if (asg_out) asg_out[m] = bi;
-        atomicAdd(&off[bi], 1);
     }
-    for (int r = tid; r < s.k; r += FIN_THREADS) {
-        const int j = min(max(kp[r], 0), s.V - 1);
-        asg[j] = r;
-        if (asg_out) asg_out[j] = r;
-        atomicAdd(&off[r], 1);
+    int ktok[FIN_PER];
+#pragma unroll
+    for (int u = 0; u < FIN_PER; ++u) {
+        const int r = tid + u * FIN_THREADS;
+        ktok[u] = -1;
+        if (r < s.k) {
+            ktok[u] = min(max(kp[r], 0), s.V - 1);
+            if (asg_out) asg_out[ktok[u]] = r;
+            atomicAdd(&off[r], 1);
+        }
     }
     __syncthreads();
     // exclusive scan of the slot histogram
@@ -404,24 +429,29 @@ __global__ __launch_bounds__(FIN_THREADS) void merge_finalize_kernel(
     if (tid == 0) so[s.k] = s.V;
     __syncthreads();
     // unordered fill (LDS cursor), then rank inside each segment to order the members ascending
-    for (int j = tid; j < s.V; j += FIN_THREADS) {
-        const int pos = atomicAdd(&off[asg[j]], 1);
-        mem[pos] = j;
+#pragma unroll
+    for (int u = 0; u < FIN_PER; ++u) {
+        if (tok[u] >= 0) { const int pos = atomicAdd(&off[slot[u]], 1); mem[pos] = (slot[u] << 14) | tok[u]; }
+        if (ktok[u] >= 0) { const int r = tid + u * FIN_THREADS; const int pos = atomicAdd(&off[r], 1); mem[pos] = (r << 14) | ktok[u]; }
     }
     __syncthreads();
     int32_t* mo = members + (size_t)b * max_V;
     for (int pos = tid; pos < s.V; pos += FIN_THREADS) {
-        const int j = mem[pos];
-        const int r = asg[j];
+        const int me = mem[pos];
+        const int r = me >> 14;
         const int start = (r == 0) ? 0 : off[r - 1];      // off[r] now holds the END of segment r
         const int end = off[r];
         int rank = 0;
-        for (int q2 = start; q2 < end; ++q2) rank += (mem[q2] < j);
-        mo[start + rank] = j;
+        for (int q2 = start; q2 < end; ++q2) rank += (mem[q2] < me);
+        mo[start + rank] = me & 0x3FFF;
     }
 }
 
 // ---- scatter-average + compaction ----------------------------------------------------------
+// One workgroup per output row.  A merged row first stages its member list in LDS (one coalesced
+// read), then streams the member rows four at a time so that eight 16-byte loads per thread are in
+// flight; accumulation order stays ascending, so the result does not depend on the unrolling.
+constexpr int SCAT_LIST = 256;     // members staged per pass
 template <typename T, int CPT>     // CPT: 16-byte chunks per thread per pass
 __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const T* __restrict__ x, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
@@ -433,6 +463,7 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int N_m = s.N - s.M;
     if (o >= N_m) return;
+    __shared__ int list[SCAT_LIST];
     const int tid = threadIdx.x;
     T* yrow = y + (size_t)(out_off[b] + o) * d;
     const int nch = d / EPC;
@@ -457,29 +488,50 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     }
     const T* xv = x + (size_t)(s.tok0 + s.vs) * d;
     const float inv = (mode == D3TOM_MERGE_MEAN) ? (float)len : 1.0f;
-    for (int c0 = tid; c0 < nch; c0 += 256 * CPT) {
+    auto add_row = [&](float (&acc)[CPT][EPC], const uint4 (&w)[CPT]) {
+#pragma unroll
+        for (int u = 0; u < CPT; ++u) {
+            if constexpr (sizeof(T) == 2) {
+                acc[u][0] += bf16_lo(w[u].x); acc[u][1] += bf16_hi(w[u].x);
+                acc[u][2] += bf16_lo(w[u].y); acc[u][3] += bf16_hi(w[u].y);
+                acc[u][4] += bf16_lo(w[u].z); acc[u][5] += bf16_hi(w[u].z);
+                acc[u][6] += bf16_lo(w[u].w); acc[u][7] += bf16_hi(w[u].w);
+            } else {
+                acc[u][0] += __uint_as_float(w[u].x); acc[u][1] += __uint_as_float(w[u].y);
+                acc[u][2] += __uint_as_float(w[u].z); acc[u][3] += __uint_as_float(w[u].w);
+            }
+        }
+    };
+    for (int cb = 0; cb < nch; cb += 256 * CPT) {         // uniform trip count: the loop body has barriers
+        const int c0 = cb + tid;
         float acc[CPT][EPC];
 #pragma unroll
         for (int u = 0; u < CPT; ++u)
 #pragma unroll
             for (int e = 0; e < EPC; ++e) acc[u][e] = 0.f;
-        for (int t = 0; t < len; ++t) {
-            const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)mo[start + t] * d);
+        for (int l0 = 0; l0 < len; l0 += SCAT_LIST) {
+            const int ln = min(SCAT_LIST, len - l0);
+            __syncthreads();
+            if (tid < ln) list[tid] = mo[start + l0 + tid];
+            __syncthreads();
+            int t = 0;
+            for (; t + 4 <= ln; t += 4) {
+                uint4 w[4][CPT];
 #pragma unroll
-            for (int u = 0; u < CPT; ++u) {
-                const int c = c0 + 256 * u;
-                if (c < nch) {
-                    const uint4 w = row[c];
-                    if constexpr (sizeof(T) == 2) {
-                        acc[u][0] += bf16_lo(w.x); acc[u][1] += bf16_hi(w.x);
-                        acc[u][2] += bf16_lo(w.y); acc[u][3] += bf16_hi(w.y);
-                        acc[u][4] += bf16_lo(w.z); acc[u][5] += bf16_hi(w.z);
-                        acc[u][6] += bf16_lo(w.w); acc[u][7] += bf16_hi(w.w);
-                    } else {
-                        acc[u][0] += __uint_as_float(w.x); acc[u][1] += __uint_as_float(w.y);
-                        acc[u][2] += __uint_as_float(w.z); acc[u][3] += __uint_as_float(w.w);
-                    }
+                for (int m = 0; m < 4; ++m) {
+                    const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)list[t + m] * d);
+#pragma unroll
+                    for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[m][u] = (c < nch) ? row[c] : make_uint4(0, 0, 0, 0); }
                 }
+#pragma unroll
+                for (int m = 0; m < 4; ++m) add_row(acc, w[m]);
+            }
+            for (; t < ln; ++t) {
+                uint4 w[CPT];
+                const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)list[t] * d);
+#pragma unroll
+                for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[u] = (c < nch) ? row[c] : make_uint4(0, 0, 0, 0); }
+                add_row(acc, w);
             }
         }
 #pragma unroll
@@ -509,13 +561,13 @@ using namespace d3tom;
 extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
                            int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
                            const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
-                           int max_N, int max_V, int max_keep, int max_pruned, int mode,
+                           int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
                            const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
                            void* ws, size_t ws_bytes, void* stream) {
     if (!x || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off || !y)
         return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || d < 1 || max_N < 1 || max_V < 1 || max_V > max_N || max_keep < 1 || max_keep > max_V ||
-        max_pruned < 0 || max_pruned > max_V)
+        max_pruned < 0 || max_pruned > max_V || max_out < 1 || max_out > max_N)
         return D3TOM_ERR_INVALID_ARG;
     if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
     if (mode != D3TOM_MERGE_MEAN && mode != D3TOM_MERGE_SUM) return D3TOM_ERR_INVALID_ARG;
@@ -533,7 +585,6 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
     int32_t* pruned = (int32_t*)(wsb + w.pruned_off);
     float* rnorm = (float*)(wsb + w.rnorm_off);
     float2* part = (float2*)(wsb + w.part_off);
-    int32_t* asg_ws = (int32_t*)(wsb + w.assign_off);
     int32_t* seg = (int32_t*)(wsb + w.seg_off);
     int32_t* mem = (int32_t*)(wsb + w.mem_off);
 
@@ -600,9 +651,9 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
 
     D3TOM_LAUNCH(MERGE_FINALIZE, st, merge_finalize_kernel<<<B, FIN_THREADS, (size_t)(max_keep + 1 + max_V) * 4, st>>>(
         seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
-        assign, asg_ws, counts, seg, mem));
+        assign, counts, seg, mem));
 
-    const dim3 gs(max_N, B);      // upper bound on output rows per sample; surplus workgroups exit at once
+    const dim3 gs(max_out, B);    // output rows per sample; surplus workgroups of shorter samples exit at once
     if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>(
             (const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, seg,

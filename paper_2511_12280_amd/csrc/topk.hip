@@ -2,10 +2,13 @@
 // the kept count; Algorithm 1, the TopK line).
 //
 // One 1024-thread workgroup per sample, the whole score vector resident in LDS as order-preserving
-// 32-bit keys.  A 4 x 8-bit most-significant-digit radix SELECT finds the k-th largest key exactly
-// (no sort), then an ordered compaction emits the kept positions ascending.  Equal keys at the
+// 32-bit keys.  A most-significant-digit radix SELECT (8 bits per pass, starting below the bits that
+// all keys share) finds the k-th largest key exactly (no sort), then an ordered compaction emits the
+// kept positions ascending.  Equal keys at the
 // threshold are taken lowest index first, which makes the selection identical to ranking by
-// (score descending, index ascending).  Integer LDS atomics only: deterministic.
+// (score descending, index ascending).  Integer LDS atomics only: deterministic.  Scores of one sample
+// share their sign and exponent bits, so the leading digits land in one or two bins; per-wave
+// histograms keep those same-address updates from serialising across the whole workgroup.
 #include "common.hpp"
 
 namespace d3tom {
@@ -43,34 +46,70 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ score_off, const int32_t* __restrict__ keep_k,
     const int32_t* __restrict__ kept_off, int max_V, int32_t* __restrict__ kept_idx, int32_t* __restrict__ slot_of) {
     extern __shared__ uint32_t ukey[];                 // [max_V]
-    __shared__ int hist[256];
+    __shared__ int whist[16][256];        // one digit histogram per wave: same-bin updates only collide inside a wave
     __shared__ int wsum[17];
-    __shared__ int sel[2];
+    __shared__ int sel[3];
+    __shared__ uint32_t wrange[32];
     const int b = blockIdx.x;
     const int s0 = score_off[b];
     const int V = min(score_off[b + 1] - s0, max_V);
     if (V <= 0) return;
     const int kk = min(max(keep_k[b], 1), V);
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
 
-    for (int j = tid; j < V; j += TOPK_THREADS) ukey[j] = order_key(scores[s0 + j]);
-    uint32_t prefix = 0, mask = 0;
-    int remaining = kk;
+    // keys, and the range they span: bits above the highest differing bit are common to all keys
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
+    for (int j = tid; j < V; j += TOPK_THREADS) {
+        const uint32_t u = order_key(scores[s0 + j]);
+        ukey[j] = u;
+        kmin = min(kmin, u); kmax = max(kmax, u);
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        kmin = min(kmin, (uint32_t)__shfl_xor((int)kmin, o, WAVE));
+        kmax = max(kmax, (uint32_t)__shfl_xor((int)kmax, o, WAVE));
+    }
+    if (lane == 0) { wrange[wave] = kmin; wrange[16 + wave] = kmax; }
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < 16; ++w) { kmin = min(kmin, wrange[w]); kmax = max(kmax, wrange[16 + w]); }
+    const uint32_t diff = kmin ^ kmax;
+    const int hi = diff ? 32 - __clz(diff) : 0;                 // number of low bits that vary
+    uint32_t mask = (hi >= 32) ? 0u : ~((hi == 0) ? 0u : ((1u << hi) - 1u));
+    uint32_t prefix = kmax & mask;
+    int remaining = kk, tot_eq = V;
+    // most-significant-digit radix select over the varying bits, 8 bits per pass
 #pragma unroll 1
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        if (tid < 256) hist[tid] = 0;
+    for (int top = hi; top > 0; top -= 8) {
+        const int shift = max(top - 8, 0);
+        const uint32_t dmask = (1u << (top - shift)) - 1u;
+        for (int t = tid; t < 16 * 256; t += TOPK_THREADS) (&whist[0][0])[t] = 0;
         __syncthreads();
-        for (int j = tid; j < V; j += TOPK_THREADS) {
-            const uint32_t u = ukey[j];
-            if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255u], 1);
+        for (int base = 0; base < V; base += TOPK_THREADS) {
+            const int j = base + tid;
+            const uint32_t u = (j < V) ? ukey[j] : 0u;
+            const bool match = (j < V) && ((u & mask) == prefix);
+            const uint32_t dg = (u >> shift) & dmask;
+            const unsigned long long mm = __ballot(match);
+            if (mm) {
+                // a whole wave on one digit would serialise on one LDS address: add it once instead
+                const int first = __ffsll((long long)mm) - 1;
+                const uint32_t d0 = (uint32_t)__shfl((int)dg, first, WAVE);
+                const unsigned long long same = __ballot(match && dg == d0);
+                if (same == mm) { if (lane == first) atomicAdd(&whist[wave][d0], __popcll(mm)); }
+                else if (match) atomicAdd(&whist[wave][dg], 1);
+            }
         }
         __syncthreads();
         if (tid < 64) {
             // lane l owns digits 255-4l .. 252-4l (descending); find the digit holding the remaining-th key
-            int c[4], tot = 0;
+            int c[4] = {0, 0, 0, 0}, tot = 0;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { c[e] = hist[255 - (4 * tid + e)]; tot += c[e]; }
+            for (int e = 0; e < 4; ++e) {
+#pragma unroll
+                for (int w = 0; w < 16; ++w) c[e] += whist[w][255 - (4 * tid + e)];
+                tot += c[e];
+            }
             int inc = tot;
 #pragma unroll
             for (int o = 1; o < 64; o <<= 1) {
@@ -80,22 +119,28 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
             int before = inc - tot;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (before < remaining && remaining <= before + c[e]) { sel[0] = 255 - (4 * tid + e); sel[1] = remaining - before; }
+                if (before < remaining && remaining <= before + c[e]) {
+                    sel[0] = 255 - (4 * tid + e); sel[1] = remaining - before; sel[2] = c[e];
+                }
                 before += c[e];
             }
         }
         __syncthreads();
         prefix |= ((uint32_t)sel[0]) << shift;
-        mask |= 255u << shift;
+        mask |= dmask << shift;
         remaining = sel[1];
+        tot_eq = sel[2];
     }
-    const uint32_t thr = prefix;       // k-th largest key; `remaining` of the keys equal to it are kept
+    const uint32_t thr = prefix;       // k-th largest key; `remaining` of the `tot_eq` keys equal to it are kept
     const int per = (V + TOPK_THREADS - 1) / TOPK_THREADS;
     const int j0 = min(tid * per, V), j1 = min(j0 + per, V);
-    int n_eq = 0;
-    for (int j = j0; j < j1; ++j) n_eq += (ukey[j] == thr);
-    int tot_eq;
-    int eq_before = block_excl_scan(n_eq, wsum, &tot_eq);
+    int eq_before = 0;
+    if (tot_eq != remaining) {         // ties straddle the threshold: lowest indices first
+        int n_eq = 0;
+        for (int j = j0; j < j1; ++j) n_eq += (ukey[j] == thr);
+        int unused;
+        eq_before = block_excl_scan(n_eq, wsum, &unused);
+    }
     int n_keep = 0;
     {
         int e = eq_before;
