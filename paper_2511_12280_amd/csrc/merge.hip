@@ -145,9 +145,21 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 // Workgroup ids are mapped to tiles per XCD: ids are dealt round-robin to the 8 XCDs, each XCD
 // owns a rectangular block of R x C tiles, so its private L2 only ever sees R row tiles and C column
 // tiles of the operands.
+// The loads are buffer loads: each lane's byte offset (row and swizzled chunk) is fixed for the whole
+// sweep and the k-slice moves through the scalar offset, so a stage costs no address arithmetic.
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
-typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 constexpr int COS_NS = 4;
+
+// The buffer-resource type and builtins exist in the device pass only; the host pass sees the kernel
+// with an empty body (it only needs the launch stub).
+#if defined(__HIP_DEVICE_COMPILE__)
+// buffer resource over [p, p + bytes), built from values the compiler can see are wave-uniform
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_uniform_rsrc(const void* p, uint32_t bytes) {
+    const uint64_t a = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+#endif
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
@@ -168,6 +180,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
     float2* __restrict__ part, int XC, int R, int C) {
+#if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BM = TM * 64;
     constexpr int STAGE = (BM + COS_BN) * 128;          // bytes per ring stage (64 bf16 = 128 B per row)
     constexpr int A_LD = BM / 32;                       // direct loads per wave and stage, A tile (8 rows each)
@@ -192,16 +205,17 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const float* rn = rnorm + (size_t)b * max_V;
     const size_t base = (size_t)(s.tok0 + s.vs) * d;
 
-    // source address of this lane for each of its direct loads (rows past the end re-read row 0; masked later)
-    const uint16_t* a_src[A_LD];
-    const uint16_t* b_src[B_LD];
+    // byte offset of this lane inside the visual block for each of its direct loads (rows past the end
+    // re-read row 0; masked later); the k-slice is added through the scalar offset
+    const __amdgpu_buffer_rsrc_t rsrc = make_uniform_rsrc(f + base, (uint32_t)((size_t)s.V * d * sizeof(uint16_t)));
+    int a_off[A_LD], b_off[B_LD];
 #pragma unroll
     for (int i = 0; i < A_LD; ++i) {
         const int row = wave * (BM / 4) + i * 8 + (lane >> 3);
         const int cg = (lane & 7) ^ ((row >> 1) & 7);
         const int p = rt * BM + row;
         const int m = (p < s.M) ? pr[p] : pr[0];
-        a_src[i] = f + base + (size_t)m * d + cg * 8;
+        a_off[i] = m * d * 2 + cg * 16;
     }
 #pragma unroll
     for (int i = 0; i < B_LD; ++i) {
@@ -209,7 +223,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         const int cg = (lane & 7) ^ ((row >> 1) & 7);
         const int r = ct * COS_BN + row;
         const int j = min(max(kp[(r < s.k) ? r : 0], 0), s.V - 1);
-        b_src[i] = f + base + (size_t)j * d + cg * 8;
+        b_off[i] = j * d * 2 + cg * 16;
     }
     for (int t = tid; t < BM; t += 256) { const int p = rt * BM + t; rnA[t] = (p < s.M) ? rn[pr[p]] : 0.f; }
     for (int t = tid; t < COS_BN; t += 256) {
@@ -220,12 +234,12 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         char* sb = ring + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(a_src[i] + kt * COS_BK),
-                                             (lds_ptr_t)(sb + (wave * (BM / 4) + i * 8) * 128), 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(sb + (wave * (BM / 4) + i * 8) * 128), 16,
+                                                     a_off[i], kt * (COS_BK * 2), 0, 0);
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
-            __builtin_amdgcn_global_load_lds((glb_ptr_t)(b_src[i] + kt * COS_BK),
-                                             (lds_ptr_t)(sb + BM * 128 + (wave * (COS_BN / 4) + i * 8) * 128), 16, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(sb + BM * 128 + (wave * (COS_BN / 4) + i * 8) * 128), 16,
+                                                     b_off[i], kt * (COS_BK * 2), 0, 0);
     };
 
     f32x16 acc[TM][2];
@@ -243,64 +257,80 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
     for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
 
-    // Rows are a power-of-two number of bytes apart, so one 128-byte k-slice of every row falls on the
-    // same memory channel.  Workgroups that run side by side on an XCD therefore start their sweep over
-    // the contraction index at staggered offsets (a dot product does not care where it starts).
     const int nkt = d / COS_BK;
-    const int rot = li % min(nkt, 16);
-    auto kslice = [&](int kt) { const int t = kt + rot; return t >= nkt ? t - nkt : t; };
-#pragma unroll
-    for (int st = 0; st < COS_NS - 1; ++st)
-        if (st < nkt) issue(kslice(st), st);
-    for (int kt = 0; kt < nkt; ++kt) {
-        if (kt + COS_NS - 2 < nkt) wait_loads_and_barrier<(COS_NS - 2) * LPS>();
-        else wait_loads_and_barrier<0>();
-        if (kt + COS_NS - 1 < nkt) issue(kslice(kt + COS_NS - 1), (kt + COS_NS - 1) % COS_NS);
+    // one stage: (optionally) start the loads of the stage COS_NS-1 ahead, then feed stage kt to the MFMAs
+    auto stage = [&](int kt, const bool prefetch) {
+        if (prefetch) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
         const char* sb = ring + (kt % COS_NS) * STAGE;
-        // all operand fragments of the stage are requested up front; the MFMAs start as the first
-        // ones arrive and run under the remaining LDS reads
-        bf16x8 af[COS_BK / 16][TM], bfr[COS_BK / 16][2];
 #pragma unroll
         for (int kk = 0; kk < COS_BK / 16; ++kk) {
+            bf16x8 af[TM], bfr[2];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[kk][i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
+                af[i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                bfr[kk][j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
-        }
-#pragma unroll
-        for (int kk = 0; kk < COS_BK / 16; ++kk)
+                bfr[j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk][i], bfr[kk][j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+        }
+    };
+#pragma unroll
+    for (int st = 0; st < COS_NS - 1; ++st)
+        if (st < nkt) issue(st, st);
+    int kt = 0;
+    for (; kt + COS_NS - 1 < nkt; ++kt) {                  // steady state: COS_NS-2 newer stages stay in flight
+        wait_loads_and_barrier<(COS_NS - 2) * LPS>();
+        stage(kt, true);
+    }
+    for (; kt < nkt; ++kt) {                               // drain
+        wait_loads_and_barrier<0>();
+        stage(kt, false);
     }
 
-    // epilogue: cosine = dot * rn_row * rn_col; per row, best (value, slot) over this tile's columns
+    // epilogue: cosine = dot * rn_row * rn_col; per row, best (value, slot) over this tile's columns.
+    // Branch-free selects, and all rows advance through each exchange step together, so the 32
+    // independent cross-lane exchanges of a step are in flight at once.
+    float bv[TM][16];
+    int bi[TM][16];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
             const float rr = rnA[row];
-            float bv = -INFINITY; int bi = 0x7FFFFFFF;
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int col = wn * 64 + j * 32 + c;
-                const int slot = ct * COS_BN + col;
-                const float v = (slot < s.k) ? acc[i][j][e] * rr * rnB[col] : -INFINITY;
-                if (v > bv) { bv = v; bi = slot; }
-            }
-#pragma unroll
-            for (int o = 1; o < 32; o <<= 1) {
-                const float v2 = __shfl_xor(bv, o, WAVE);
-                const int i2 = __shfl_xor(bi, o, WAVE);
-                if (v2 > bv || (v2 == bv && i2 < bi)) { bv = v2; bi = i2; }
-            }
-            if (c == 0) red[wn][row] = make_float2(bv, __int_as_float(bi));
+            const int col0 = wn * 64 + c, col1 = col0 + 32;
+            const int s0 = ct * COS_BN + col0, s1 = s0 + 32;
+            const float v0 = (s0 < s.k) ? acc[i][0][e] * rr * rnB[col0] : -INFINITY;
+            const float v1 = (s1 < s.k) ? acc[i][1][e] * rr * rnB[col1] : -INFINITY;
+            const bool t1 = v1 > v0;                       // equal values: the lower slot stays
+            bv[i][e] = t1 ? v1 : v0;
+            bi[i][e] = t1 ? s1 : s0;
         }
+#pragma unroll
+    for (int o = 1; o < 32; o <<= 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float v2 = __shfl_xor(bv[i][e], o, WAVE);
+                const int i2 = __shfl_xor(bi[i][e], o, WAVE);
+                const bool take = (v2 > bv[i][e]) | ((v2 == bv[i][e]) & (i2 < bi[i][e]));
+                bv[i][e] = take ? v2 : bv[i][e];
+                bi[i][e] = take ? i2 : bi[i][e];
+            }
+    }
+    if (c == 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                red[wn][row] = make_float2(bv[i][e], __int_as_float(bi[i][e]));
+            }
     }
     __syncthreads();
     for (int t = tid; t < BM; t += 256) {
@@ -312,6 +342,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
             part[((size_t)b * NCT + ct) * max_V + p] = a;
         }
     }
+#endif
 }
 
 // ---- cosine + argmax, generic: one workgroup per pruned row, waves stride over the kept slots ---
@@ -612,7 +643,7 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<float><<<gn, 256, 0, st>>>(
             (const float*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm));
 
-    const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0);
+    const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0) && ((size_t)max_V * d_sim * 2 < ((size_t)1 << 31));
     if (mfma) {
         const int nct = ceil_div(max_keep, COS_BN);
         // 128-row tiles unless that leaves most of the 256 CUs idle
