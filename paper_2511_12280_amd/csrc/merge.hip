@@ -188,7 +188,6 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     constexpr int LPS = A_LD + B_LD;                    // loads per wave and stage
     extern __shared__ __attribute__((aligned(16))) char ring[];
     __shared__ float rnA[BM], rnB[COS_BN];
-    __shared__ float2 red[2][BM];
 
     const int per = 8 * R * C;
     const int b = blockIdx.x / per;
@@ -310,37 +309,36 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
             bv[i][e] = t1 ? v1 : v0;
             bi[i][e] = t1 ? s1 : s0;
         }
+    // The 64 candidates of a row (32 lanes x 2 wave columns) meet in LDS (the ring is free now): every
+    // lane stores its 16*TM candidates, then two threads per row scan 32 candidates each in ascending slot
+    // order.  Rows are padded to 33 entries so that the scan of 32 different rows hits 32 different banks.
+    __syncthreads();                                           // all waves are done with the ring
+    float2* cand = reinterpret_cast<float2*>(ring);            // [BM][2][33]
 #pragma unroll
-    for (int o = 1; o < 32; o <<= 1) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const float v2 = __shfl_xor(bv[i][e], o, WAVE);
-                const int i2 = __shfl_xor(bi[i][e], o, WAVE);
-                const bool take = (v2 > bv[i][e]) | ((v2 == bv[i][e]) & (i2 < bi[i][e]));
-                bv[i][e] = take ? v2 : bv[i][e];
-                bi[i][e] = take ? i2 : bi[i][e];
-            }
-    }
-    if (c == 0) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                red[wn][row] = make_float2(bv[i][e], __int_as_float(bi[i][e]));
-            }
-    }
-    __syncthreads();
-    for (int t = tid; t < BM; t += 256) {
-        const int p = rt * BM + t;
-        if (p < s.M) {
-            float2 a = red[0][t];
-            const float2 b2 = red[1][t];
-            if (b2.x > a.x) a = b2;                       // equal values: lower slot (wn = 0) stays
-            part[((size_t)b * NCT + ct) * max_V + p] = a;
+        for (int e = 0; e < 16; ++e) {
+            const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+            cand[(row * 2 + wn) * 33 + c] = make_float2(bv[i][e], __int_as_float(bi[i][e]));
         }
+    __syncthreads();
+    for (int t = tid; t < BM * 2; t += 256) {
+        const int row = t >> 1, half = t & 1;                  // half 0: slots of wave column 0 (lower slots)
+        const float2* cr = cand + (row * 2 + half) * 33;
+        float best = -INFINITY; int bidx = 0x7FFFFFFF;
+#pragma unroll 8
+        for (int q2 = 0; q2 < 32; ++q2) {
+            const float2 a = cr[q2];
+            const int ia = __float_as_int(a.y);
+            const bool take = (a.x > best) | ((a.x == best) & (ia < bidx));
+            best = take ? a.x : best; bidx = take ? ia : bidx;
+        }
+        const float ov = __shfl_xor(best, 1, WAVE);
+        const int oi = __shfl_xor(bidx, 1, WAVE);
+        const bool take = (ov > best) | ((ov == best) & (oi < bidx));
+        best = take ? ov : best; bidx = take ? oi : bidx;
+        const int p = rt * BM + row;
+        if (half == 0 && p < s.M) part[((size_t)b * NCT + ct) * max_V + p] = make_float2(best, __int_as_float(bidx));
     }
 #endif
 }
