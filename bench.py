@@ -205,6 +205,8 @@ def main():
     ap.add_argument("--workload", default="lavida_3645_sweep")
     ap.add_argument("--also", default="llada_v_1024", help="second workload reported beside the first ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy, the known-size reference for HBM counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: the path is a single-GPU kernel chain (run with --gpus 1)", file=sys.stderr)
@@ -212,6 +214,12 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if args.calibrate_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
     wl, res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
     dom = res["kernels"][res["dominant"]]
     line = {

@@ -53,7 +53,7 @@ __device__ __forceinline__ void att_wait_and_barrier() {
 template <int DH>
 __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ cu, int H, float scale2, uint16_t* __restrict__ o) {
+    const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o) {
     constexpr int KS = DH / 16;                 // k-steps of the first product
     constexpr int DT = DH / 32;                 // 32-dim tiles of O^T
     constexpr int ROWB = DH * 2;                // bytes per K / V row in LDS (unpadded, chunks swizzled)
@@ -64,7 +64,12 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     constexpr int STAGE = 2 * TILE;
     extern __shared__ __attribute__((aligned(16))) char ring[];
 
-    const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; all query tiles of one (sample, head) are given
+    // ids of the same residue so that the head's K and V are fetched into one XCD's L2 only.
+    const int xcd = blockIdx.x & 7, li = blockIdx.x >> 3;
+    const int hb = (li / nqt) * 8 + xcd, qt = li % nqt;         // hb = sample * H + head
+    if (hb >= H * nB) return;
+    const int h = hb % H, b = hb / H;
     const int tok0 = cu[b];
     const int n = cu[b + 1] - tok0;
     if (qt * ATT_BQ >= n) return;
@@ -283,7 +288,8 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
     hipStream_t st = (hipStream_t)stream;
     const float scale2 = scale * LOG2E;
     if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
-        const dim3 g(ceil_div(max_seqlen, ATT_BQ), H, B);
+        const int nqt = ceil_div(max_seqlen, ATT_BQ);
+        const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)ATT_NS * 2 * ATT_BK * dh * 2;
         static bool attr_set = false;
         if (!attr_set) {
@@ -296,10 +302,10 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
         }
         if (dh == 128)
             D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<128><<<g, 256, lds, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, scale2, (uint16_t*)o));
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
         else
             D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<64><<<g, 256, lds, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, scale2, (uint16_t*)o));
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
     } else {
         const dim3 g(max_seqlen, H, B);
         if (dt == D3TOM_F32)
