@@ -103,7 +103,7 @@ def algorithmic(wl, lay):
     move / compute: K once per sweep, the visual rows once, input + output rows once, 4 n^2 d for attention)."""
     eb = 4 if wl.dtype == "f32" else 2
     d = wl.d
-    out = {k: [0.0, 0.0] for k in ("imp_stats", "imp_scores", "imp_finish", "topk_select", "merge_prep", "merge_norms",
+    out = {k: [0.0, 0.0] for k in ("imp_stats", "imp_scores", "imp_finish", "topk_select", "merge_norms",
                                    "cos_argmax", "merge_finalize", "merge_scatter", "attend")}
     for N, V, k, D, Nm in zip(lay.N, lay.V, lay.keep, lay.D, lay.Nm):
         M = V - k
@@ -111,7 +111,6 @@ def algorithmic(wl, lay):
         out["imp_scores"][0] += (V + D) * d * eb + 4 * V;   out["imp_scores"][1] += 2.0 * D * V * d
         out["imp_finish"][0] += 4 * V * (wl.H + 1)
         out["topk_select"][0] += 4 * V + 4 * k + 4 * V
-        out["merge_prep"][0] += 4 * k + 4 * M
         out["merge_norms"][0] += V * d * eb + 4 * V
         out["cos_argmax"][0] += V * d * eb;                 out["cos_argmax"][1] += 2.0 * M * k * d
         out["merge_finalize"][0] += 8 * M + 12 * V

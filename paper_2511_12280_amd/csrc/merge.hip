@@ -2,8 +2,8 @@
 // FORALL block and the "Remove positions" line).
 //
 // Stages, all on the caller's stream:
-//   prep      complement of kept_idx -> ascending list of pruned visual tokens          (1 WG / sample)
-//   norms     1 / ||row|| of every visual row of the similarity features               (1 wave / row)
+//   norms     1 / ||row|| of every visual row of the similarity features (1 wave / row); one extra
+//             workgroup per sample turns kept_idx into the ascending list of pruned visual tokens
 //   cosine    pruned x kept similarity GEMM on MFMA 32x32x16 bf16 with the argmax fused into the
 //             epilogue: only (best value, best slot) per (pruned row, 128-slot column tile) ever
 //             leaves the registers; the M x k matrix is never written
@@ -76,45 +76,64 @@ __device__ __forceinline__ int fin_excl_scan(int v, int* wsum /*[17]*/, int* tot
     return wsum[wave] + inc - v;
 }
 
-// ---- prep: ascending list of pruned visual tokens -------------------------------------------
-__global__ __launch_bounds__(FIN_THREADS) void merge_prep_kernel(
-    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
-    const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off, int max_V, int max_keep,
-    int32_t* __restrict__ pruned) {
-    extern __shared__ int lds[];          // flags [max_V]
-    __shared__ int wsum[17];
-    const int b = blockIdx.x;
-    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
-    if (s.V <= 0) return;
-    for (int j = threadIdx.x; j < s.V; j += FIN_THREADS) lds[j] = 0;
+// ---- norms + pruned list ------------------------------------------------------------------------
+// One wave per visual row computes 1 / ||row||.  The LAST workgroup of each sample instead builds the
+// ascending list of pruned visual tokens (the complement of kept_idx) from a bitmask in LDS; it runs
+// beside the norm workgroups, so the list costs no launch of its own.
+__device__ __forceinline__ void build_pruned_list(const SampleGeom& s, const int32_t* __restrict__ kp,
+                                                  int32_t* __restrict__ out) {
+    __shared__ uint32_t bits[D3TOM_MAX_VISUAL / 32];
+    __shared__ int wtot[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nw = (s.V + 31) >> 5;
+    for (int w = tid; w < nw; w += 256) bits[w] = 0u;
     __syncthreads();
-    for (int r = threadIdx.x; r < s.k; r += FIN_THREADS) lds[min(max(kept_idx[kept_off[b] + r], 0), s.V - 1)] = 1;
+    for (int r = tid; r < s.k; r += 256) {
+        const int j = min(max(kp[r], 0), s.V - 1);
+        atomicOr(&bits[j >> 5], 1u << (j & 31));
+    }
     __syncthreads();
-    const int per = (s.V + FIN_THREADS - 1) / FIN_THREADS;
-    const int j0 = min((int)threadIdx.x * per, s.V), j1 = min(j0 + per, s.V);
+    // thread t owns words [t*per, (t+1)*per): count its pruned tokens, scan, emit
+    const int per = (nw + 255) / 256;
+    const int w0 = min(tid * per, nw), w1 = min(w0 + per, nw);
     int n = 0;
-    for (int j = j0; j < j1; ++j) n += (lds[j] == 0);
-    int tot;
-    int p = fin_excl_scan(n, wsum, &tot);
-    int32_t* out = pruned + (size_t)b * max_V;
-    for (int j = j0; j < j1; ++j)
-        if (lds[j] == 0) out[p++] = j;
+    for (int w = w0; w < w1; ++w) {
+        uint32_t inv = ~bits[w];
+        if (w == nw - 1 && (s.V & 31)) inv &= (1u << (s.V & 31)) - 1u;
+        n += __popc(inv);
+    }
+    int inc = n;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(inc, o, WAVE);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) wtot[wave] = inc;
+    __syncthreads();
+    int p = inc - n;
+    for (int w = 0; w < wave; ++w) p += wtot[w];
+    for (int w = w0; w < w1; ++w) {
+        uint32_t inv = ~bits[w];
+        if (w == nw - 1 && (s.V & 31)) inv &= (1u << (s.V & 31)) - 1u;
+        while (inv) { const int b = __ffs((int)inv) - 1; out[p++] = w * 32 + b; inv &= inv - 1u; }
+    }
 }
 
-// ---- norms: one wave per visual row --------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void merge_norms_kernel(
     const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
-    const int32_t* __restrict__ vis_count, int max_V, float* __restrict__ rnorm) {
+    const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    int max_V, int max_keep, float* __restrict__ rnorm, int32_t* __restrict__ pruned) {
     const int b = blockIdx.y;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    if (blockIdx.x == gridDim.x - 1) {
+        if (s.V > 0) build_pruned_list(s, kept_idx + kept_off[b], pruned + (size_t)b * max_V);
+        return;
+    }
     const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
     const int lane = threadIdx.x & 63;
-    const int tok0 = seq_off[b];
-    const int N = seq_off[b + 1] - tok0;
-    const int vs = min(max(vis_start[b], 0), N);
-    const int V = min(min(vis_count[b], max_V), N - vs);
-    if (j >= V) return;
-    const T* row = f + (size_t)(tok0 + vs + j) * d;
+    if (j >= s.V) return;
+    const T* row = f + (size_t)(s.tok0 + s.vs + j) * d;
     constexpr int EPC = 16 / sizeof(T);       // elements per 16-byte chunk
     float ss = 0.f;
     for (int c = lane; c < d / EPC; c += 64) {
@@ -619,9 +638,7 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
 
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)merge_prep_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                D3TOM_MAX_VISUAL * 4) != hipSuccess ||
-            hipFuncSetAttribute((const void*)merge_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute((const void*)merge_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (2 * D3TOM_MAX_VISUAL + 1) * 4) != hipSuccess ||
             hipFuncSetAttribute((const void*)cos_argmax_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 COS_NS * (64 + COS_BN) * 128) != hipSuccess ||
@@ -631,15 +648,13 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
         attr_set = true;
     }
 
-    D3TOM_LAUNCH(MERGE_PREP, st, merge_prep_kernel<<<B, FIN_THREADS, (size_t)max_V * 4, st>>>(
-        seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned));
-    const dim3 gn(ceil_div(max_V, 4), B);
+    const dim3 gn(ceil_div(max_V, 4) + 1, B);          // + 1: the workgroup that builds the pruned list
     if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>(
-            (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm));
+            (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned));
     else
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<float><<<gn, 256, 0, st>>>(
-            (const float*)sim, d_sim, seq_off, vis_start, vis_count, max_V, rnorm));
+            (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned));
 
     const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0) && ((size_t)max_V * d_sim * 2 < ((size_t)1 << 31));
     if (mfma) {
