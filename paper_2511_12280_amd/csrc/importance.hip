@@ -79,6 +79,12 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
     __shared__ float2 wstat[4][D3TOM_MAX_DECIDERS];
 
+    // decider positions of the first group are requested before the key fragments, so that the
+    // position -> query-row chain runs beside the key loads instead of behind them
+    int pos0[IMP_NB];
+#pragma unroll
+    for (int nb = 0; nb < IMP_NB; ++nb) pos0[nb] = (nb * 16 + r < D) ? dec[nb * 16 + r] : 0;
+
     bf16x8 kf[IMP_SUB][KS];
     bool kvalid[IMP_SUB];
 #pragma unroll
@@ -95,7 +101,7 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
         for (int nb = 0; nb < IMP_NB; ++nb) {
             const int i = (db0 + nb) * 16 + r;
             const bool qv = i < D;
-            const int pos = min(max(qv ? dec[i] : 0, 0), N - 1);
+            const int pos = min(max(db0 == 0 ? pos0[nb] : (qv ? dec[i] : 0), 0), N - 1);
             load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf[nb]);
         }
 #pragma unroll
@@ -161,16 +167,9 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
     __shared__ float c_lds[D3TOM_MAX_DECIDERS];
 
-    bf16x8 kf[IMP_SUB][KS];
-    float acc_s[IMP_SUB];
+    int pos0[IMP_NB];
 #pragma unroll
-    for (int s = 0; s < IMP_SUB; ++s) {
-        const int j = key_base + (wave * IMP_SUB + s) * 16 + r;
-        const bool kv = j < V;
-        const uint16_t* row = k + ((size_t)(tok0 + vs + (kv ? j : 0)) * H + h) * DH;
-        load_frag<DH>(row, g, kv, kf[s]);
-        acc_s[s] = 0.f;
-    }
+    for (int nb = 0; nb < IMP_NB; ++nb) pos0[nb] = (nb * 16 + r < D) ? dec[nb * 16 + r] : 0;
     // log2-sum-exp2 of every decider row of this head, key chunks combined in ascending order
     const int nch = (N + IMP_KC - 1) / IMP_KC;
     for (int t = threadIdx.x; t < D; t += 256) {
@@ -185,6 +184,16 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
         }
         c_lds[t] = m + log2f(z);
     }
+    bf16x8 kf[IMP_SUB][KS];
+    float acc_s[IMP_SUB];
+#pragma unroll
+    for (int s = 0; s < IMP_SUB; ++s) {
+        const int j = key_base + (wave * IMP_SUB + s) * 16 + r;
+        const bool kv = j < V;
+        const uint16_t* row = k + ((size_t)(tok0 + vs + (kv ? j : 0)) * H + h) * DH;
+        load_frag<DH>(row, g, kv, kf[s]);
+        acc_s[s] = 0.f;
+    }
     __syncthreads();
 
     const int nblk = (D + 15) >> 4;
@@ -194,7 +203,7 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
         for (int nb = 0; nb < IMP_NB; ++nb) {
             const int i = (db0 + nb) * 16 + r;
             const bool qv = i < D;
-            const int pos = min(max(qv ? dec[i] : 0, 0), N - 1);
+            const int pos = min(max(db0 == 0 ? pos0[nb] : (qv ? dec[i] : 0), 0), N - 1);
             load_frag<DH>(q + ((size_t)(tok0 + pos) * H + h) * DH, g, qv, qf[nb]);
         }
 #pragma unroll
