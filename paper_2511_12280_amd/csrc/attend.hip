@@ -14,14 +14,19 @@
 // fed in the order the accumulator holds it; V^T is read from LDS in that same order.
 //
 // Workgroup = 4 waves x 32 queries of one head, 64 keys per LDS stage.  K and V tiles go HBM/L2 -> LDS
-// with direct loads (global_load_lds, no register staging) into a two-stage ring, so the loads of the
-// next stage overlap the MFMAs of the current one and one s_barrier per stage suffices; rows are
-// unpadded and their 16-byte chunks XOR-swizzled by the row index instead.  Softmax state and
-// accumulators are float32; two workgroups fit a CU.
+// with direct loads (buffer_load ... lds, no register staging; rows past the end of the sample load as
+// zeros through the buffer bounds check) into a two-stage ring; rows are unpadded and their 16-byte
+// chunks XOR-swizzled by the row index instead.  Per tile a wave requests all 16 K fragments before the
+// first MFMA, runs the two accumulation chains of S^T interleaved, requests the V^T fragments of the
+// first 32 keys and starts the direct loads of the next stage, then does the softmax arithmetic while
+// those are in flight (measured on gfx950: direct loads overlap vector-ALU work but not MFMAs), and
+// finally the 16 MFMAs of the second product.  Softmax state and accumulators are float32; two
+// workgroups fit a CU.
 //
 // The generic path (float32 or any head size) is one workgroup per (query, head) with a chunked
 // online softmax in plain float arithmetic.
 #include "common.hpp"
+#include <type_traits>
 
 namespace d3tom {
 
@@ -41,19 +46,45 @@ __device__ __forceinline__ att_short4 lds_read_tr16(const char* p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lp)p);
 }
 
-template <int N>
+// all of this wave's direct loads have landed and all its LDS reads are done; then meet the other waves
 __device__ __forceinline__ void att_wait_and_barrier() {
-    if constexpr (N == 0) asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else {
-        static_assert(N == 8, "add the wait count");
-        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
+
+#if defined(__HIP_DEVICE_COMPILE__)
+// buffer resource over [p, p + bytes), built from values the compiler can see are wave-uniform
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t att_uniform_rsrc(const void* p, uint32_t bytes) {
+    const uint64_t a = (uint64_t)p;
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)a), hi = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc((void*)(((uint64_t)hi << 32) | lo), 0, (int)__builtin_amdgcn_readfirstlane(bytes), 0x00020000);
+}
+// One wave-wide direct load HBM/L2 -> LDS: lane i fetches 16 bytes at byte offset `voff` of the buffer
+// (zeros when that is past the end of the buffer) into LDS byte lds_base + 16 i.  Issued from inline
+// assembly on purpose: the waits for these loads are placed by hand (att_wait_and_barrier), and the
+// compiler, when it sees such a load, makes every later transposing LDS read wait for all of them.
+__device__ __forceinline__ void att_direct_load(__amdgpu_buffer_rsrc_t rsrc, int voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_base), "v"(voff), "s"(rsrc) : "memory", "m0");
+}
+// the two lanes (l, l ^ 32) that share a query column combine their values: after the swap of the upper
+// half of one copy with the lower half of the other, the two results hold {own, partner} in some order
+__device__ __forceinline__ float att_pair_max(float x) {
+    typedef unsigned att_u2 __attribute__((ext_vector_type(2)));
+    const att_u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float att_pair_sum(float x) {
+    typedef unsigned att_u2 __attribute__((ext_vector_type(2)));
+    const att_u2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+#endif
 
 template <int DH>
 __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o) {
+#if defined(__HIP_DEVICE_COMPILE__)
     constexpr int KS = DH / 16;                 // k-steps of the first product
     constexpr int DT = DH / 32;                 // 32-dim tiles of O^T
     constexpr int ROWB = DH * 2;                // bytes per K / V row in LDS (unpadded, chunks swizzled)
@@ -64,8 +95,6 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     constexpr int STAGE = 2 * TILE;
     extern __shared__ __attribute__((aligned(16))) char ring[];
 
-    // Workgroup ids are dealt round-robin to the 8 XCDs; all query tiles of one (sample, head) are given
-    // ids of the same residue so that the head's K and V are fetched into one XCD's L2 only.
     const int xcd = blockIdx.x & 7, li = blockIdx.x >> 3;
     const int hb = (li / nqt) * 8 + xcd, qt = li % nqt;         // hb = sample * H + head
     if (hb >= H * nB) return;
@@ -79,8 +108,11 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     const size_t rs = (size_t)H * DH;                      // token stride (elements)
     const uint16_t* kb = k + (size_t)tok0 * rs + (size_t)h * DH;
     const uint16_t* vb = v + (size_t)tok0 * rs + (size_t)h * DH;
+    // this head's K / V rows of this sample; a row index >= n is past the end and loads as zeros
+    const uint32_t span = (uint32_t)(((size_t)(n - 1) * rs + DH) * 2);
+    const __amdgpu_buffer_rsrc_t rk = att_uniform_rsrc(kb, span), rv = att_uniform_rsrc(vb, span);
+    const int row_bytes = (int)(rs * 2);
 
-    // Q^T fragments: lane (query c, g) holds dims kk*16 + 8g .. +7
     const int qrow = qt * ATT_BQ + wave * 32 + c;
     const bool qvalid = qrow < n;
     bf16x8 qf[KS];
@@ -100,49 +132,86 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     float m_run = -INFINITY, l_run = 0.f;       // running max of the RAW logits, running sum of exp2
 
     // direct loads: lane -> (row, chunk position); the chunk fetched into position p of row r is
-    // p ^ (r & 15) for K (operand reads walk 16+ consecutive rows) and p ^ ((r & 3) * 4) for V
+    // p ^ (r mod NCHK) for K (operand reads walk 16+ consecutive rows) and p ^ ((r & 3) * 4) for V
     // (transposing reads touch 4 consecutive rows per 16-lane group)
-    const int ld_row = wave * (ATT_BK / 4) + lane / NCHK;       // + i * RPI
     const int ld_pos = lane % NCHK;
+    int k_off[LD], v_off[LD];                   // byte offsets inside the head's K / V for key0 = 0
+#pragma unroll
+    for (int i = 0; i < LD; ++i) {
+        const int r = wave * (ATT_BK / 4) + lane / NCHK + i * RPI;
+        k_off[i] = r * row_bytes + (((ld_pos ^ (r & 15)) & (NCHK - 1)) << 4);
+        v_off[i] = r * row_bytes + (((ld_pos ^ ((r & 3) * 4)) & (NCHK - 1)) << 4);
+    }
+    const uint32_t ring0 = (uint32_t)(size_t)(att_lds_ptr_t)ring;
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (ATT_BK / 4) * ROWB);
     auto issue = [&](int key0, int stage) {
-        char* sb = ring + stage * STAGE;
+        const int kofs = key0 * row_bytes;
 #pragma unroll
         for (int i = 0; i < LD; ++i) {
-            const int r = ld_row + i * RPI;
-            const int key = min(key0 + r, n - 1);                // rows past the end re-read the last key (masked)
-            const int kc = (ld_pos ^ (r & 15)) & (NCHK - 1);
-            const int vc = (ld_pos ^ ((r & 3) * 4)) & (NCHK - 1);
-            __builtin_amdgcn_global_load_lds((att_glb_ptr_t)(kb + (size_t)key * rs + kc * 8),
-                                             (att_lds_ptr_t)(sb + (wave * (ATT_BK / 4) + i * RPI) * ROWB), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((att_glb_ptr_t)(vb + (size_t)key * rs + vc * 8),
-                                             (att_lds_ptr_t)(sb + TILE + (wave * (ATT_BK / 4) + i * RPI) * ROWB), 16, 0, 0);
+            att_direct_load(rk, k_off[i] + kofs, wave_lds + stage * STAGE + i * RPI * ROWB);
+            att_direct_load(rv, v_off[i] + kofs, wave_lds + stage * STAGE + TILE + i * RPI * ROWB);
         }
     };
+    // K operand fragments: lane (key row c, g) reads chunk (2 kk + g) of its row, swizzled by the row
+    int k_addr[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) k_addr[kk] = c * ROWB + ((((kk * 2 + g) ^ (c & 15)) & (NCHK - 1)) << 4);
     // transposing-read geometry of this lane: 16-lane group -> (g, dim half), lane in group -> (row j, 4-dim quad t)
     const int tr_j = (lane & 15) >> 2, tr_t = lane & 3, tr_half = (lane >> 4) & 1;
+    int v_addr[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) {
+        const int chunk = t * 4 + tr_half * 2 + (tr_t >> 1);
+        v_addr[t] = TILE + (g * 4 + tr_j) * ROWB + (tr_t % 2) * 8 + (((chunk ^ (tr_j * 4)) & (NCHK - 1)) << 4);
+    }
 
     const int ntile = (n + ATT_BK - 1) / ATT_BK;
-    issue(0, 0);
-    for (int it = 0; it < ntile; ++it) {
+    // one 64-key tile out of ring stage STG (a compile-time constant so that every LDS offset folds
+    // into the instruction)
+    auto tile = [&](auto stg_c, int it) {
+        constexpr int STG = decltype(stg_c)::value;
         const int key0 = it * ATT_BK;
-        att_wait_and_barrier<0>();                             // stage `it` has landed; stage it-1 is free
-        if (it + 1 < ntile) issue(key0 + ATT_BK, (it + 1) % ATT_NS);
-        const char* sb = ring + (it % ATT_NS) * STAGE;
+        att_wait_and_barrier();                             // stage STG has landed; the other stage is free
+        const char* sb = ring + STG * STAGE;
 
-        // S^T = K Q^T for two 32-key tiles
+        // all K fragments of the tile are requested before the first MFMA
+        bf16x8 kf[2][KS];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int kk = 0; kk < KS; ++kk)
+                kf[kt][kk] = *reinterpret_cast<const bf16x8*>(sb + k_addr[kk] + kt * 32 * ROWB);
+        __builtin_amdgcn_sched_barrier(0);
+        // S^T = K Q^T for two 32-key blocks, the two accumulation chains interleaved
         f32x16 st[2];
 #pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
+        for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) st[kt][e] = 0.f;
-            const int r = kt * 32 + c;
-            const char* krow = sb + r * ROWB;
 #pragma unroll
-            for (int kk = 0; kk < KS; ++kk) {
-                const bf16x8 af = *reinterpret_cast<const bf16x8*>(krow + ((((kk * 2 + g) ^ (r & 15)) & (NCHK - 1)) << 4));
-                st[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, qf[kk], st[kt], 0, 0, 0);
-            }
+        for (int kk = 0; kk < KS; ++kk) {
+            st[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][kk], qf[kk], st[0], 0, 0, 0);
+            st[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][kk], qf[kk], st[1], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        // V^T fragments of the first 32 keys are requested now and land during the softmax arithmetic
+        att_short4 vf[2][2][DT][2];                 // [kt][hh][t][a/b]
+        auto read_v = [&](int kt) {
+#pragma unroll
+            for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+                for (int t = 0; t < DT; ++t) {
+                    const char* pa = sb + v_addr[t] + (kt * 32 + hh * 16) * ROWB;
+                    vf[kt][hh][t][0] = lds_read_tr16(pa);
+                    vf[kt][hh][t][1] = lds_read_tr16(pa + 8 * ROWB);
+                }
+        };
+        read_v(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // the loads of the next stage start here, beside the softmax arithmetic: direct loads and MFMAs
+        // slow each other down, direct loads and vector-ALU work do not
+        if (it + 1 < ntile) issue(key0 + ATT_BK, STG ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
         // online softmax in base 2 on the raw logits; element e of st[kt]: key kt*32 + (e/4)*8 + 4g + e%4, query c
         if (key0 + ATT_BK > n) {
 #pragma unroll
@@ -158,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
             for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, st[kt][e]);
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, WAVE));
+        tmax = att_pair_max(tmax);
         const float m_new = fmaxf(m_run, tmax);            // finite: every stage holds >= 1 valid key
         const float ms = m_new * scale2;
         float psum = 0.f;
@@ -170,7 +239,6 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
                 st[kt][e] = p;
                 psum += p;
             }
-        psum += __shfl_xor(psum, 32, WAVE);
         if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {      // some query of this wave moved its max
             const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
             l_run *= alpha;
@@ -179,10 +247,12 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
 #pragma unroll
                 for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
         }
-        l_run += psum;
+        l_run += psum;                               // per-lane partial; the two halves meet after the last tile
         m_run = m_new;
+        __builtin_amdgcn_sched_barrier(0);
+        read_v(1);
+        __builtin_amdgcn_sched_barrier(0);
         // O^T += V^T P^T
-        const char* vt = sb + TILE;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -190,24 +260,26 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
                 bf16x8 pf;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) pf[j] = (__bf16)st[kt][hh * 8 + j];
-                // k-slots j = 0..3 of lane (., g): keys kofs + j; j = 4..7: keys kofs + 8 + (j - 4)
-                const int key_a = kt * 32 + hh * 16 + g * 4 + tr_j;
-                const int key_b = key_a + 8;
-                const char* ra = vt + key_a * ROWB + tr_t % 2 * 8;
-                const char* rb = vt + key_b * ROWB + tr_t % 2 * 8;
-                const int sw_a = (key_a & 3) * 4, sw_b = (key_b & 3) * 4;
 #pragma unroll
                 for (int t = 0; t < DT; ++t) {
-                    const int chunk = t * 4 + tr_half * 2 + (tr_t >> 1);
-                    const att_short4 va = lds_read_tr16(ra + (((chunk ^ sw_a) & (NCHK - 1)) << 4));
-                    const att_short4 vb2 = lds_read_tr16(rb + (((chunk ^ sw_b) & (NCHK - 1)) << 4));
-                    union { short s[8]; bf16x8 b; } u;
-                    u.s[0] = va[0]; u.s[1] = va[1]; u.s[2] = va[2]; u.s[3] = va[3];
-                    u.s[4] = vb2[0]; u.s[5] = vb2[1]; u.s[6] = vb2[2]; u.s[7] = vb2[3];
-                    ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(u.b, pf, ot[t], 0, 0, 0);
+                    const att_short4 va = vf[kt][hh][t][0], vb2 = vf[kt][hh][t][1];
+                    typedef __attribute__((__vector_size__(8 * sizeof(short)))) short att_short8;
+                    const att_short8 v8 = __builtin_shufflevector(va, vb2, 0, 1, 2, 3, 4, 5, 6, 7);
+                    ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pf, ot[t], 0, 0, 0);
                 }
             }
+    };
+    // The query fragments must have arrived before the first direct load is issued: otherwise the
+    // compiler's own wait for them would sit inside the loop, where it would also wait for the direct
+    // loads of the next stage.
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" :: "v"(qf[kk]));
+    issue(0, 0);
+    for (int it = 0; it < ntile; it += 2) {
+        tile(std::integral_constant<int, 0>{}, it);
+        if (it + 1 < ntile) tile(std::integral_constant<int, 1>{}, it + 1);
     }
+    l_run = att_pair_sum(l_run);
     if (!qvalid) return;
     const float inv = 1.0f / l_run;
     uint16_t* op = o + (size_t)(tok0 + qrow) * rs + (size_t)h * DH;
@@ -220,8 +292,8 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
             w.y = pack_bf16x2(ot[t][e4 * 4 + 2] * inv, ot[t][e4 * 4 + 3] * inv);
             *reinterpret_cast<uint2*>(op + t * 32 + e4 * 8 + g * 4) = w;
         }
+#endif
 }
-
 // generic: one workgroup per (query, head), keys in chunks of 256, plain float online softmax
 template <typename T>
 __global__ __launch_bounds__(256) void attend_generic_kernel(
@@ -287,7 +359,9 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
     if (dh > 256 || (dt == D3TOM_BF16 ? (dh % 8) : (dh % 4))) return D3TOM_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     const float scale2 = scale * LOG2E;
-    if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
+    // the tiled kernel addresses one sample's K / V rows with 32-bit byte offsets
+    const bool fits32 = ((size_t)max_seqlen + ATT_BK) * (size_t)H * (size_t)dh * 2 < ((size_t)1 << 31);
+    if (dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32) {
         const int nqt = ceil_div(max_seqlen, ATT_BQ);
         const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)ATT_NS * 2 * ATT_BK * dh * 2;

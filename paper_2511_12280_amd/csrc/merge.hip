@@ -280,20 +280,28 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     auto stage = [&](int kt, const bool prefetch) {
         if (prefetch) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
         const char* sb = ring + (kt % COS_NS) * STAGE;
-#pragma unroll
-        for (int kk = 0; kk < COS_BK / 16; ++kk) {
-            bf16x8 af[TM], bfr[2];
+        // operand fragments are read one k-step ahead of the MFMAs that use them, so the LDS latency
+        // of step kk + 1 is covered by the matrix work of step kk
+        bf16x8 af[2][TM], bfr[2][2];
+        auto read_frags = [&](int kk, int buf) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
-                af[i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
+                af[buf][i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                bfr[j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
+                bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < COS_BK / 16; ++kk) {
+            if (kk + 1 < COS_BK / 16) read_frags(kk + 1, (kk + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 #pragma unroll
