@@ -196,6 +196,19 @@ def oracle_baseline(wl, dev):
                        f"all five stages, {spent:.1f} s of oracle time")
 
 
+# HBM bytes per launch (fetch + write), averaged over the sweep, from the two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE) summarised in profiles/lavida_3645_sweep_hbm_traffic.txt; counters scaled by what
+# they read for a plain 256 MiB copy.  Counters cannot be read from inside this process, so the figures
+# are carried here and refreshed together with that profile.
+MEASURED_HBM_TRAFFIC = {
+    "lavida_3645_sweep": {
+        "imp_stats": 33.35e6, "imp_scores": 33.88e6, "imp_finish": 0.51e6, "topk_select": 0.05e6,
+        "merge_norms": 29.96e6, "cos_argmax": 98.57e6, "merge_finalize": 0.24e6, "merge_scatter": 41.32e6,
+        "attend": 40.20e6,
+    },
+}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -230,7 +243,8 @@ def main():
                                f"{wl.H}x{wl.dh} heads, batch {wl.B}, {wl.note}", "timed": "inputs resident in HBM"},
         "merge_layer_us": res["merge_layer_us"], "attend_us": res["attend_us"],
         "roofline": {"kernel": res["dominant"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
-                     "unit": dom["unit"], "frac": dom["frac"], "traffic": None, "avg_us": dom["avg_us"]},
+                     "unit": dom["unit"], "frac": dom["frac"],
+                     "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get(res["dominant"]), "avg_us": dom["avg_us"]},
         "kernels": res["kernels"],
     }
     if "cpu_baseline" in res:

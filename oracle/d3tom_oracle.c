@@ -14,7 +14,7 @@
  * wall-clock time is an OpenMP "parallel for" over independent outer
  * iterations (heads, rows); each iteration is the sequential definition.
  *
- * Pinned by tests/test_oracle_*.py: closed forms, invariants, textbook special
+ * Pinned by tests/test_oracle_pins.py: closed forms, invariants, textbook special
  * cases, library routines and brute force.  The paper prints no worked numeric
  * example of the merge, so no printed values exist to compare with.
  */
