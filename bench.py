@@ -104,7 +104,7 @@ def algorithmic(wl, lay):
     eb = 4 if wl.dtype == "f32" else 2
     d = wl.d
     out = {k: [0.0, 0.0] for k in ("imp_stats", "imp_scores", "imp_finish", "topk_select", "merge_norms",
-                                   "cos_argmax", "merge_finalize", "merge_scatter", "attend")}
+                                   "cos_argmax", "merge_assign", "merge_scatter", "attend")}
     for N, V, k, D, Nm in zip(lay.N, lay.V, lay.keep, lay.D, lay.Nm):
         M = V - k
         out["imp_stats"][0] += (N + D) * d * eb;            out["imp_stats"][1] += 2.0 * D * N * d
@@ -113,7 +113,7 @@ def algorithmic(wl, lay):
         out["topk_select"][0] += 4 * V + 4 * k + 4 * V
         out["merge_norms"][0] += V * d * eb + 4 * V
         out["cos_argmax"][0] += V * d * eb;                 out["cos_argmax"][1] += 2.0 * M * k * d
-        out["merge_finalize"][0] += 8 * M + 12 * V
+        out["merge_assign"][0] += 8 * M * max(1, -(-k // 128)) + 8 * V
         out["merge_scatter"][0] += (N + Nm) * d * eb + 4 * V
         out["attend"][0] += 4 * Nm * d * eb;                out["attend"][1] += 4.0 * Nm * Nm * d
     return out
@@ -203,7 +203,7 @@ def oracle_baseline(wl, dev):
 MEASURED_HBM_TRAFFIC = {
     "lavida_3645_sweep": {
         "imp_stats": 33.35e6, "imp_scores": 33.88e6, "imp_finish": 0.51e6, "topk_select": 0.05e6,
-        "merge_norms": 29.96e6, "cos_argmax": 98.57e6, "merge_finalize": 0.24e6, "merge_scatter": 41.32e6,
+        "merge_norms": 29.96e6, "cos_argmax": 98.57e6, "merge_assign": 0.24e6, "merge_scatter": 41.32e6,
         "attend": 40.20e6,
     },
 }

@@ -73,7 +73,7 @@ inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 // ---- optional per-kernel timing (d3tom_profile_*): HIP events around each launch when enabled ----
 namespace prof {
 enum Kernel {
-    IMP_STATS = 0, IMP_SCORES, IMP_FINISH, TOPK_SELECT, MERGE_NORMS, COS_ARGMAX, MERGE_FINALIZE, MERGE_SCATTER, ATTEND,
+    IMP_STATS = 0, IMP_SCORES, IMP_FINISH, TOPK_SELECT, MERGE_NORMS, COS_ARGMAX, MERGE_ASSIGN, MERGE_SCATTER, ATTEND,
     NUM_KERNELS
 };
 extern bool g_enabled;

@@ -7,12 +7,12 @@
 //   cosine    pruned x kept similarity GEMM on MFMA 32x32x16 bf16 with the argmax fused into the
 //             epilogue: only (best value, best slot) per (pruned row, 128-slot column tile) ever
 //             leaves the registers; the M x k matrix is never written
-//   finalize  argmax across column tiles (ascending, strict '>' : ties go to the lowest slot), then a
-//             counting sort of all visual tokens by destination slot into a CSR (segment offsets +
-//             member list, members ascending inside each segment)                       (1 WG / sample)
-//   scatter   one workgroup per OUTPUT row: merged rows stream their members with 16-byte loads and
-//             accumulate in float32 in ascending member order, other rows are copied; one store per
-//             element, no atomics, so the result is bit-reproducible
+//   assign    argmax across column tiles (ascending, strict '>' : ties go to the lowest slot) for every
+//             pruned token, own slot for every kept token -> token -> slot table   (1 thread / token)
+//   scatter   one workgroup per OUTPUT row: a merged row scans the token -> slot table for its members
+//             (ascending token order), streams them with 16-byte loads and accumulates in float32 in
+//             that order, other rows are copied; one store per element, no atomics, so the result is
+//             bit-reproducible
 //
 // All similarities are taken on the rows as given (assignment first, aggregation afterwards).
 #include "common.hpp"
@@ -21,10 +21,9 @@ namespace d3tom {
 
 constexpr int COS_BN = 128;        // kept slots per column tile
 constexpr int COS_BK = 64;         // contraction elements per LDS stage
-constexpr int FIN_THREADS = 1024;
 
 struct MergeWs {
-    size_t pruned_off, rnorm_off, part_off, seg_off, mem_off, total;
+    size_t pruned_off, rnorm_off, part_off, mem_off, total;
     int NCT;
 };
 __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
@@ -34,8 +33,7 @@ __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
     w.pruned_off = o; o += align_up((size_t)B * max_V * 4, 256);
     w.rnorm_off = o;  o += align_up((size_t)B * max_V * 4, 256);
     w.part_off = o;   o += align_up((size_t)B * w.NCT * max_V * 8, 256);
-    w.seg_off = o;    o += align_up((size_t)B * (max_V + 1) * 4, 256);
-    w.mem_off = o;    o += align_up((size_t)B * max_V * 4, 256);
+    w.mem_off = o;    o += align_up((size_t)B * align_up((size_t)max_V, 4) * 4, 256);   // token -> slot table, rows of 4-entry groups
     w.total = o;
     return w;
 }
@@ -52,28 +50,6 @@ __device__ __forceinline__ SampleGeom sample_geom(int b, const int32_t* seq_off,
     s.k = min(min(kept_off[b + 1] - kept_off[b], max_keep), s.V);
     s.M = s.V - s.k;
     return s;
-}
-
-// exclusive workgroup scan of one int per thread (1024 threads)
-__device__ __forceinline__ int fin_excl_scan(int v, int* wsum /*[17]*/, int* total) {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int inc = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o, WAVE);
-        if (lane >= o) inc += t;
-    }
-    __syncthreads();
-    if (lane == 63) wsum[wave] = inc;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int w = 0; w < FIN_THREADS / 64; ++w) { const int t = wsum[w]; wsum[w] = run; run += t; }
-        wsum[16] = run;
-    }
-    __syncthreads();
-    *total = wsum[16];
-    return wsum[wave] + inc - v;
 }
 
 // ---- norms + pruned list ------------------------------------------------------------------------
@@ -408,132 +384,124 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
     }
 }
 
-// ---- finalize: argmax over column tiles, CSR of all visual tokens by slot -------------------
-// Every thread owns up to FIN_PER visual tokens of each kind (pruned list entry / kept slot) and keeps
-// their destination slot in registers between the histogram and the fill, so nothing is re-read from
-// global memory.  Members are packed (slot << 14 | token) while they sit in LDS.
-constexpr int FIN_PER = D3TOM_MAX_VISUAL / FIN_THREADS;     // 16
-__global__ __launch_bounds__(FIN_THREADS) void merge_finalize_kernel(
+// ---- assignment: argmax over column tiles -> destination slot of every visual token ----------------
+// One thread per visual token: entry i < M is the i-th pruned token (best slot over the column tiles,
+// ascending tiles and strict '>' so that the lowest slot wins ties), entry i >= M is kept slot i - M
+// (its own token).  slot_of_tok[b][token] is what the scatter kernel scans.
+__global__ __launch_bounds__(256) void merge_assign_kernel(
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
     const int32_t* __restrict__ vis_off, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float2* __restrict__ part, int NCT, int tiled,
-    int32_t* __restrict__ assign_out, int32_t* __restrict__ counts, int32_t* __restrict__ seg_off,
-    int32_t* __restrict__ members) {
-    extern __shared__ int lds[];      // off[max_keep + 1] | mem[max_V]
-    __shared__ int wsum[17];
-    const int b = blockIdx.x;
+    int32_t* __restrict__ assign_out, int32_t* __restrict__ slot_of_tok) {
+    const int b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
-    if (s.V <= 0 || s.k <= 0) return;
-    int* off = lds;
-    int* mem = lds + (max_keep + 1);
-    const int tid = threadIdx.x;
-    const int32_t* pr = pruned + (size_t)b * max_V;
-    const int32_t* kp = kept_idx + kept_off[b];
-    int32_t* asg_out = assign_out ? assign_out + vis_off[b] : nullptr;
-    const int nct = tiled ? (s.k + COS_BN - 1) / COS_BN : 1;
-    const float2* pb = part + (size_t)b * NCT * max_V;
-
-    for (int r = tid; r <= s.k; r += FIN_THREADS) off[r] = 0;
-    __syncthreads();
-    int tok[FIN_PER], slot[FIN_PER];                   // pruned tokens of this thread and where they go
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (s.k <= 0 || i >= s.V) return;
+    int tok, slot;
+    if (i < s.M) {
+        const int nct = tiled ? (s.k + COS_BN - 1) / COS_BN : 1;
+        const float2* pb = part + (size_t)b * NCT * max_V;
+        float bv = -INFINITY; int bi = 0;
+        for (int c0 = 0; c0 < nct; c0 += 8) {              // 8 independent loads in flight
+            float2 a[8];
 #pragma unroll
-    for (int u = 0; u < FIN_PER; ++u) {
-        const int p = tid + u * FIN_THREADS;
-        tok[u] = -1; slot[u] = 0;
-        if (p < s.M) {
-            float bv = -INFINITY; int bi = 0;
-            for (int c0 = 0; c0 < nct; c0 += 4) {          // 4 independent loads in flight; ascending tiles,
-                float2 a[4];                                // strict '>' keeps the lowest slot on ties
+            for (int w = 0; w < 8; ++w) a[w] = (c0 + w < nct) ? pb[(size_t)(c0 + w) * max_V + i] : make_float2(-INFINITY, 0.f);
 #pragma unroll
-                for (int w = 0; w < 4; ++w) a[w] = (c0 + w < nct) ? pb[(size_t)(c0 + w) * max_V + p] : make_float2(-INFINITY, 0.f);
-#pragma unroll
-                for (int w = 0; w < 4; ++w) if (a[w].x > bv) { bv = a[w].x; bi = __float_as_int(a[w].y); }
-            }
-            bi = min(max(bi, 0), s.k - 1);
-            tok[u] = pr[p]; slot[u] = bi;
-            if (asg_out) asg_out[tok[u]] = bi;
-            atomicAdd(&off[bi], 1);
+            for (int w = 0; w < 8; ++w) if (a[w].x > bv) { bv = a[w].x; bi = __float_as_int(a[w].y); }
         }
+        slot = min(max(bi, 0), s.k - 1);
+        tok = min(max(pruned[(size_t)b * max_V + i], 0), s.V - 1);
+    } else {
+        slot = i - s.M;
+        tok = min(max(kept_idx[kept_off[b] + slot], 0), s.V - 1);
     }
-    int ktok[FIN_PER];
-#pragma unroll
-    for (int u = 0; u < FIN_PER; ++u) {
-        const int r = tid + u * FIN_THREADS;
-        ktok[u] = -1;
-        if (r < s.k) {
-            ktok[u] = min(max(kp[r], 0), s.V - 1);
-            if (asg_out) asg_out[ktok[u]] = r;
-            atomicAdd(&off[r], 1);
-        }
-    }
-    __syncthreads();
-    // exclusive scan of the slot histogram
-    const int per = (s.k + FIN_THREADS - 1) / FIN_THREADS;
-    const int r0 = min(tid * per, s.k), r1 = min(r0 + per, s.k);
-    int n = 0;
-    for (int r = r0; r < r1; ++r) n += off[r];
-    int tot;
-    int run = fin_excl_scan(n, wsum, &tot);
-    int32_t* so = seg_off + (size_t)b * (max_V + 1);
-    for (int r = r0; r < r1; ++r) {
-        const int cnt = off[r];
-        if (counts) counts[kept_off[b] + r] = cnt;
-        so[r] = run;
-        off[r] = run;
-        run += cnt;
-    }
-    if (tid == 0) so[s.k] = s.V;
-    __syncthreads();
-    // unordered fill (LDS cursor), then rank inside each segment to order the members ascending
-#pragma unroll
-    for (int u = 0; u < FIN_PER; ++u) {
-        if (tok[u] >= 0) { const int pos = atomicAdd(&off[slot[u]], 1); mem[pos] = (slot[u] << 14) | tok[u]; }
-        if (ktok[u] >= 0) { const int r = tid + u * FIN_THREADS; const int pos = atomicAdd(&off[r], 1); mem[pos] = (r << 14) | ktok[u]; }
-    }
-    __syncthreads();
-    int32_t* mo = members + (size_t)b * max_V;
-    for (int pos = tid; pos < s.V; pos += FIN_THREADS) {
-        const int me = mem[pos];
-        const int r = me >> 14;
-        const int start = (r == 0) ? 0 : off[r - 1];      // off[r] now holds the END of segment r
-        const int end = off[r];
-        int rank = 0;
-        for (int q2 = start; q2 < end; ++q2) rank += (mem[q2] < me);
-        mo[start + rank] = me & 0x3FFF;
-    }
+    slot_of_tok[(size_t)b * align_up((size_t)max_V, 4) + tok] = slot;
+    if (assign_out) assign_out[vis_off[b] + tok] = slot;
 }
 
 // ---- scatter-average + compaction ----------------------------------------------------------
-// One workgroup per output row.  A merged row first stages its member list in LDS (one coalesced
-// read), then streams the member rows four at a time so that eight 16-byte loads per thread are in
-// flight; accumulation order stays ascending, so the result does not depend on the unrolling.
+// One workgroup per output row.  A merged row first finds its members: the four waves scan the
+// token -> slot table of the sample (a quarter each, coalesced), keep the matches in ascending token
+// order (ballot + popcount, no atomics) and the four pieces are joined into one list in LDS.  The member
+// rows are then streamed four at a time so that eight 16-byte loads per thread are in flight;
+// accumulation order is ascending token index, so the result does not depend on the unrolling.  A slot
+// with more members than the LDS list holds is processed in windows of SCAT_LIST members (re-scan).
 constexpr int SCAT_LIST = 256;     // members staged per pass
+constexpr int SCAT_WAVE = SCAT_LIST / 4;
 template <typename T, int CPT>     // CPT: 16-byte chunks per thread per pass
 __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const T* __restrict__ x, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const int32_t* __restrict__ seg_off,
-    const int32_t* __restrict__ members, T* __restrict__ y, int32_t* __restrict__ src_pos) {
+    int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const int32_t* __restrict__ slot_of_tok,
+    T* __restrict__ y, int32_t* __restrict__ counts, int32_t* __restrict__ src_pos) {
     constexpr int EPC = 16 / sizeof(T);
     const int o = blockIdx.x, b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int N_m = s.N - s.M;
     if (o >= N_m) return;
     __shared__ int list[SCAT_LIST];
-    const int tid = threadIdx.x;
+    __shared__ int stage[4][SCAT_WAVE];
+    __shared__ int wcnt[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     T* yrow = y + (size_t)(out_off[b] + o) * d;
     const int nch = d / EPC;
-    int src = -1, start = 0, len = 1;
-    const int32_t* mo = members + (size_t)b * max_V;
+    int src = -1, len = 1, r = 0;
+    // token -> slot table of this sample, read four entries per lane; a wave takes a contiguous part
+    // of it (a multiple of 256 entries so that every lane takes part in each ballot)
+    const int4* sot4 = reinterpret_cast<const int4*>(slot_of_tok + (size_t)b * align_up((size_t)max_V, 4));
+    const int part_len = ((s.V + 1023) >> 10) << 8;
+    const int e0 = wave * part_len;
+    const int n_it = part_len >> 8;
+    int wbase = 0;                                         // members found by the waves before this one
+    bool fits = true;
+    // scan this wave's part: fn(token, ordinal among this wave's matches) for every match, ascending
+    auto scan = [&](auto&& fn) {
+        int cnt = 0;
+        for (int it0 = 0; it0 < n_it; it0 += 4) {
+            int4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = e0 + (it0 + u) * 256 + lane * 4;
+                v[u] = (it0 + u < n_it && i < s.V) ? sot4[i >> 2] : make_int4(-1, -1, -1, -1);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = e0 + (it0 + u) * 256 + lane * 4;
+                const bool m0 = v[u].x == r, m1 = (v[u].y == r) && (i + 1 < s.V), m2 = (v[u].z == r) && (i + 2 < s.V),
+                           m3 = (v[u].w == r) && (i + 3 < s.V);
+                const unsigned long long lt = (1ull << lane) - 1ull;
+                const unsigned long long b0 = __builtin_amdgcn_ballot_w64(m0), b1 = __builtin_amdgcn_ballot_w64(m1),
+                                         b2 = __builtin_amdgcn_ballot_w64(m2), b3 = __builtin_amdgcn_ballot_w64(m3);
+                int ord = cnt + __popcll(b0 & lt) + __popcll(b1 & lt) + __popcll(b2 & lt) + __popcll(b3 & lt);
+                if (m0) fn(i, ord++);
+                if (m1) fn(i + 1, ord++);
+                if (m2) fn(i + 2, ord++);
+                if (m3) fn(i + 3, ord++);
+                cnt += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
+            }
+        }
+        return cnt;
+    };
     if (o < s.vs) src = o;
     else if (o >= s.vs + s.k) src = o + s.M;
     else {
-        const int r = o - s.vs;
-        const int32_t* so = seg_off + (size_t)b * (max_V + 1);
-        start = so[r];
-        len = so[r + 1] - start;
-        if (tid == 0 && src_pos) src_pos[out_off[b] + o] = s.vs + min(max(kept_idx[kept_off[b] + r], 0), s.V - 1);
-        if (len <= 1) src = s.vs + mo[start];             // nothing absorbed: bit-exact copy
+        r = o - s.vs;
+        const int cnt = scan([&](int tok, int ord) { if (ord < SCAT_WAVE) stage[wave][ord] = tok; });
+        if (lane == 0) wcnt[wave] = cnt;
+        __syncthreads();
+        len = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
+        fits = wcnt[0] <= SCAT_WAVE && wcnt[1] <= SCAT_WAVE && wcnt[2] <= SCAT_WAVE && wcnt[3] <= SCAT_WAVE;
+        for (int w = 0; w < wave; ++w) wbase += wcnt[w];
+        const int kept_tok = min(max(kept_idx[kept_off[b] + r], 0), s.V - 1);
+        if (tid == 0) {
+            if (src_pos) src_pos[out_off[b] + o] = s.vs + kept_tok;
+            if (counts) counts[kept_off[b] + r] = len;
+        }
+        if (len <= 1) src = s.vs + kept_tok;               // nothing absorbed: bit-exact copy
+        else if (fits) {
+            if (lane < cnt) list[wbase + lane] = stage[wave][lane];
+            __syncthreads();
+        }
     }
     if (src >= 0) {
         if (tid == 0 && src_pos && (o < s.vs || o >= s.vs + s.k)) src_pos[out_off[b] + o] = src;
@@ -542,6 +510,10 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
         for (int c = tid; c < nch; c += 256) out[c] = in[c];
         return;
     }
+    // members with ordinal in [win0, win0 + SCAT_LIST) -> list (only when the first scan did not fit)
+    auto fill_window = [&](int win0) {
+        scan([&](int tok, int ord) { const int pos = wbase + ord - win0; if (pos >= 0 && pos < SCAT_LIST) list[pos] = tok; });
+    };
     const T* xv = x + (size_t)(s.tok0 + s.vs) * d;
     const float inv = (mode == D3TOM_MERGE_MEAN) ? (float)len : 1.0f;
     auto add_row = [&](float (&acc)[CPT][EPC], const uint4 (&w)[CPT]) {
@@ -567,9 +539,11 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
             for (int e = 0; e < EPC; ++e) acc[u][e] = 0.f;
         for (int l0 = 0; l0 < len; l0 += SCAT_LIST) {
             const int ln = min(SCAT_LIST, len - l0);
-            __syncthreads();
-            if (tid < ln) list[tid] = mo[start + l0 + tid];
-            __syncthreads();
+            if (!fits) {                                   // uniform
+                __syncthreads();
+                fill_window(l0);
+                __syncthreads();
+            }
             int t = 0;
             for (; t + 4 <= ln; t += 4) {
                 uint4 w[4][CPT];
@@ -641,14 +615,11 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
     int32_t* pruned = (int32_t*)(wsb + w.pruned_off);
     float* rnorm = (float*)(wsb + w.rnorm_off);
     float2* part = (float2*)(wsb + w.part_off);
-    int32_t* seg = (int32_t*)(wsb + w.seg_off);
     int32_t* mem = (int32_t*)(wsb + w.mem_off);
 
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)merge_finalize_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (2 * D3TOM_MAX_VISUAL + 1) * 4) != hipSuccess ||
-            hipFuncSetAttribute((const void*)cos_argmax_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        if (hipFuncSetAttribute((const void*)cos_argmax_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 COS_NS * (64 + COS_BN) * 128) != hipSuccess ||
             hipFuncSetAttribute((const void*)cos_argmax_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 COS_NS * (128 + COS_BN) * 128) != hipSuccess)
@@ -701,18 +672,19 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
                 rnorm, w.NCT, part));
     }
 
-    D3TOM_LAUNCH(MERGE_FINALIZE, st, merge_finalize_kernel<<<B, FIN_THREADS, (size_t)(max_keep + 1 + max_V) * 4, st>>>(
+    const dim3 ga(ceil_div(max_V, 256), B);
+    D3TOM_LAUNCH(MERGE_ASSIGN, st, merge_assign_kernel<<<ga, 256, 0, st>>>(
         seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
-        assign, counts, seg, mem));
+        assign, mem));
 
     const dim3 gs(max_out, B);    // output rows per sample; surplus workgroups of shorter samples exit at once
     if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>(
-            (const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, seg,
-            mem, (uint16_t*)y, src_pos));
+            (const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, mem,
+            (uint16_t*)y, counts, src_pos));
     else
         D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<float, 2><<<gs, 256, 0, st>>>(
-            (const float*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, seg, mem,
-            (float*)y, src_pos));
+            (const float*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, mem,
+            (float*)y, counts, src_pos));
     return D3TOM_OK;
 }

@@ -188,6 +188,15 @@ def test_edge_counts():
     c2 = W.random_case(32, 60, 128, 1, 5, 50, 2, dtype="bf16", centres=1, noise=0.0)
     step, S, kept, mout, stats = _chain([c2], [5], "bf16")
     np.testing.assert_array_equal(mout["counts"][0], [46, 1, 1, 1, 1])
+    # one slot with far more members than one staging pass of the scatter kernel holds (several windows,
+    # windows that straddle the parts of the table scanned by different waves), in both merge modes
+    c3 = W.random_case(33, 1530, 2 * 128, 2, 12, 1500, 4, dtype="bf16", centres=7)
+    for mode in ("mean", "sum"):
+        step, S, kept, mout, stats = _chain([c3], [1], "bf16", mode=mode)
+        assert mout["counts"][0][0] == 1500 and mout["y"][0].shape[0] == 31
+    c4 = W.random_case(34, 1210, 128, 1, 5, 1200, 2, dtype="bf16", centres=1, noise=0.0)
+    step, S, kept, mout, stats = _chain([c4], [5], "bf16")
+    np.testing.assert_array_equal(mout["counts"][0], [1196, 1, 1, 1, 1])
 
 
 def test_bitwise_determinism():
