@@ -56,6 +56,28 @@ __device__ __forceinline__ int wave_sum_i(int v) {
     return v;
 }
 
+// Reductions over the 16 lanes of a DPP row (lanes 16 i .. 16 i + 15), every lane ends with the result.
+// Four data-parallel-primitive steps inside the vector ALU (no LDS traffic): swap neighbours, swap
+// pairs, mirror inside each half row, mirror the whole row.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_update_dpp(0, (int)__float_as_uint(x), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float row16_max(float v) {
+    v = fmaxf(v, dpp_move<0xB1>(v));     // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_move<0x4E>(v));     // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_move<0x141>(v));    // row_half_mirror
+    v = fmaxf(v, dpp_move<0x140>(v));    // row_mirror
+    return v;
+}
+__device__ __forceinline__ float row16_sum(float v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    return v;
+}
+
 // Combine two (running max, running sum of exp2) pairs.  -inf max means "empty".
 __device__ __forceinline__ void lse2_combine(float& m, float& z, float m2, float z2) {
     float mn = fmaxf(m, m2);

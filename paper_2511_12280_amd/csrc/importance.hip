@@ -124,15 +124,13 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
                 float mx = l2[0][e];
 #pragma unroll
                 for (int s = 1; s < IMP_SUB; ++s) mx = fmaxf(mx, l2[s][e]);
-#pragma unroll
-                for (int o = 1; o < 16; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, WAVE));
+                mx = row16_max(mx);
                 float zz = 0.f;
                 if (mx != -INFINITY) {
 #pragma unroll
                     for (int s = 0; s < IMP_SUB; ++s) zz += __builtin_amdgcn_exp2f(l2[s][e] - mx);
                 }
-#pragma unroll
-                for (int o = 1; o < 16; o <<= 1) zz += __shfl_xor(zz, o, WAVE);
+                zz = row16_sum(zz);
                 if (r == 0) wstat[wave][(db0 + nb) * 16 + 4 * g + e] = make_float2(mx, zz);
             }
         }
