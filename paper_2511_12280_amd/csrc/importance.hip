@@ -21,8 +21,10 @@
 
 namespace d3tom {
 
-constexpr int IMP_KC = 256;                    // keys per workgroup (4 waves x SUB sub-tiles x 16)
-constexpr int IMP_SUB = IMP_KC / (4 * 16);
+// keys per workgroup (4 waves x SUB sub-tiles x 16): every workgroup re-fetches the decider rows of its
+// head, so few large chunks (one workgroup per CU at 3.7k tokens x 32 heads) beat many small ones
+constexpr int IMP_KC_STATS = 512, IMP_SUB_STATS = IMP_KC_STATS / (4 * 16);
+constexpr int IMP_KC_SCORES = 512, IMP_SUB_SCORES = IMP_KC_SCORES / (4 * 16);
 
 struct ImpWs {
     size_t part_off, sp_off, cnt_off, c_off, total;
@@ -30,10 +32,10 @@ struct ImpWs {
 };
 __host__ inline ImpWs imp_ws_layout(int B, int max_N, int max_V, int H, int max_D) {
     ImpWs w;
-    w.NCH = ceil_div(max_N, IMP_KC);
-    w.NCHV = ceil_div(max_V, IMP_KC);
+    w.NCH = ceil_div(max_N, IMP_KC_STATS);
+    w.NCHV = ceil_div(max_V, IMP_KC_SCORES);
     w.DPAD = ceil_div(max_D, 16) * 16;
-    w.VPAD = w.NCHV * IMP_KC;
+    w.VPAD = w.NCHV * IMP_KC_SCORES;
     size_t o = 0;
     w.part_off = o; o += align_up((size_t)B * H * w.NCH * w.DPAD * sizeof(float2), 256);
     w.sp_off = o;   o += align_up((size_t)B * H * w.VPAD * sizeof(float), 256);
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
     const int N = seq_off[b + 1] - tok0;
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
-    const int key_base = chunk * IMP_KC;
+    const int key_base = chunk * IMP_KC_STATS;
     if (key_base >= N || D <= 0) return;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
@@ -85,11 +87,11 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
 #pragma unroll
     for (int nb = 0; nb < IMP_NB; ++nb) pos0[nb] = (nb * 16 + r < D) ? dec[nb * 16 + r] : 0;
 
-    bf16x8 kf[IMP_SUB][KS];
-    bool kvalid[IMP_SUB];
+    bf16x8 kf[IMP_SUB_STATS][KS];
+    bool kvalid[IMP_SUB_STATS];
 #pragma unroll
-    for (int s = 0; s < IMP_SUB; ++s) {
-        const int key = key_base + (wave * IMP_SUB + s) * 16 + r;
+    for (int s = 0; s < IMP_SUB_STATS; ++s) {
+        const int key = key_base + (wave * IMP_SUB_STATS + s) * 16 + r;
         kvalid[s] = key < N;
         const uint16_t* row = k + ((size_t)(tok0 + (kvalid[s] ? key : 0)) * H + h) * DH;
         load_frag<DH>(row, g, kvalid[s], kf[s]);
@@ -108,9 +110,9 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
         for (int nb = 0; nb < IMP_NB; ++nb) {
             if (db0 + nb >= nblk) break;
             // l2[s][e]: scaled logit of decider row (db0+nb)*16 + 4g + e and key column r of sub-tile s
-            f32x4 l2[IMP_SUB];
+            f32x4 l2[IMP_SUB_STATS];
 #pragma unroll
-            for (int s = 0; s < IMP_SUB; ++s) {
+            for (int s = 0; s < IMP_SUB_STATS; ++s) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk)
@@ -123,12 +125,12 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
             for (int e = 0; e < 4; ++e) {
                 float mx = l2[0][e];
 #pragma unroll
-                for (int s = 1; s < IMP_SUB; ++s) mx = fmaxf(mx, l2[s][e]);
+                for (int s = 1; s < IMP_SUB_STATS; ++s) mx = fmaxf(mx, l2[s][e]);
                 mx = row16_max(mx);
                 float zz = 0.f;
                 if (mx != -INFINITY) {
 #pragma unroll
-                    for (int s = 0; s < IMP_SUB; ++s) zz += __builtin_amdgcn_exp2f(l2[s][e] - mx);
+                    for (int s = 0; s < IMP_SUB_STATS; ++s) zz += __builtin_amdgcn_exp2f(l2[s][e] - mx);
                 }
                 zz = row16_sum(zz);
                 if (r == 0) wstat[wave][(db0 + nb) * 16 + 4 * g + e] = make_float2(mx, zz);
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
     const int32_t* dec = dec_idx + dec_off[b];
     const int vs = min(max(vis_start[b], 0), N);
     const int V = min(min(vis_count[b], max_V), N - vs);
-    const int key_base = chunk * IMP_KC;
+    const int key_base = chunk * IMP_KC_SCORES;
     if (key_base >= V || D <= 0) return;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
@@ -169,24 +171,24 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
 #pragma unroll
     for (int nb = 0; nb < IMP_NB; ++nb) pos0[nb] = (nb * 16 + r < D) ? dec[nb * 16 + r] : 0;
     // log2-sum-exp2 of every decider row of this head, key chunks combined in ascending order
-    const int nch = (N + IMP_KC - 1) / IMP_KC;
+    const int nch = (N + IMP_KC_STATS - 1) / IMP_KC_STATS;
     for (int t = threadIdx.x; t < D; t += 256) {
         const float2* p = part + ((size_t)(b * H + h) * NCH) * DPAD + t;
         float m = -INFINITY, z = 0.f;
-        for (int c0 = 0; c0 < nch; c0 += 8) {              // 8 independent loads in flight, combined in order
-            float2 a[8];
+        for (int c0 = 0; c0 < nch; c0 += 16) {             // 16 independent loads in flight, combined in order
+            float2 a[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) a[u] = (c0 + u < nch) ? p[(size_t)(c0 + u) * DPAD] : make_float2(-INFINITY, 0.f);
+            for (int u = 0; u < 16; ++u) a[u] = (c0 + u < nch) ? p[(size_t)(c0 + u) * DPAD] : make_float2(-INFINITY, 0.f);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) lse2_combine(m, z, a[u].x, a[u].y);
+            for (int u = 0; u < 16; ++u) lse2_combine(m, z, a[u].x, a[u].y);
         }
         c_lds[t] = m + log2f(z);
     }
-    bf16x8 kf[IMP_SUB][KS];
-    float acc_s[IMP_SUB];
+    bf16x8 kf[IMP_SUB_SCORES][KS];
+    float acc_s[IMP_SUB_SCORES];
 #pragma unroll
-    for (int s = 0; s < IMP_SUB; ++s) {
-        const int j = key_base + (wave * IMP_SUB + s) * 16 + r;
+    for (int s = 0; s < IMP_SUB_SCORES; ++s) {
+        const int j = key_base + (wave * IMP_SUB_SCORES + s) * 16 + r;
         const bool kv = j < V;
         const uint16_t* row = k + ((size_t)(tok0 + vs + (kv ? j : 0)) * H + h) * DH;
         load_frag<DH>(row, g, kv, kf[s]);
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
                 cc[e] = (row < D) ? c_lds[row] : INFINITY;       // padded rows contribute exp2(-inf) = 0
             }
 #pragma unroll
-            for (int s = 0; s < IMP_SUB; ++s) {
+            for (int s = 0; s < IMP_SUB_SCORES; ++s) {
                 f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < KS; ++kk)
@@ -226,11 +228,11 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
     }
     float* sp_row = sp + (size_t)(b * H + h) * VPAD;
 #pragma unroll
-    for (int s = 0; s < IMP_SUB; ++s) {
+    for (int s = 0; s < IMP_SUB_SCORES; ++s) {
         float v = acc_s[s];
         v += __shfl_xor(v, 16, WAVE);
         v += __shfl_xor(v, 32, WAVE);
-        if (g == 0) sp_row[key_base + (wave * IMP_SUB + s) * 16 + r] = v;
+        if (g == 0) sp_row[key_base + (wave * IMP_SUB_SCORES + s) * 16 + r] = v;
     }
 }
 
