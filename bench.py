@@ -173,6 +173,50 @@ def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
     return wl, res
 
 
+def run_kv_cache(wl_name: str, steps: int, warmup: int):
+    """d3tom_merge_kv (Section 4.4) on a cache of the workload's prompt + visual rows: key cache = the
+    synthetic hidden rows (they carry the cluster structure the routing sees), value cache = N(0,1) rows,
+    kept sets drawn at the sweep's keep ratios.  One launch set per step; merge-only time."""
+    from paper_2511_12280_amd import binding as B
+    from paper_2511_12280_amd import workloads as W
+    wl = W.WORKLOADS[wl_name]
+    g = W.SampleGen(wl)
+    s = g.step(32)
+    n = wl.P + wl.V
+    rng = np.random.default_rng(11)
+    kc = B.to_device(s["x"][:n], wl.dtype)
+    vc = B.to_device(W.round_to(rng.standard_normal((n, wl.d)).astype(np.float32), wl.dtype), wl.dtype)
+    lays, kepts = [], []
+    for sch in W.sweep_schedule(wl):
+        k = B.d3tom_keep_count(wl.V, sch["keep_ratio"])
+        lays.append(B.Layout([n], [wl.P], [wl.V], [[0]], [k]))
+        kepts.append(torch.from_numpy(np.sort(rng.choice(wl.V, size=k, replace=False)).astype(np.int32)).cuda())
+    mx = max(l.sum_Nm for l in lays)
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    ko = torch.zeros((mx, wl.d), dtype=tdt, device="cuda"); vo = torch.zeros_like(ko)
+    counts = torch.zeros(wl.V, dtype=torch.int32, device="cuda")
+    ws = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_MERGE, 1, n, wl.V, wl.H, wl.dh, 1))
+    def step(i):
+        j = i % len(lays)
+        B.d3tom_merge_kv(kc, vc, lays[j], kepts[j], B.D3TOM_MERGE_MEAN, ko, vo, None, counts, None, ws)
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    B.d3tom_profile_enable(True)
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    prof = B.d3tom_profile_collect()
+    B.d3tom_profile_enable(False)
+    return dict(merge_kv_us=round(elapsed * 1e6 / steps, 2), cache_rows=n,
+                kernels={k: round(ms * 1e3 / c, 3) for k, (ms, c) in prof.items() if c})
+
+
 def oracle_baseline(wl, dev):
     """The fp64 oracle, as it stands, on the host cores: whole steps of the workload (all five stages),
     taken evenly over the sweep, until about 12 s of CPU time have been spent."""
@@ -254,6 +298,7 @@ def main():
         line["also"] = {args.also: {"steps_per_s": round(r2["steps_per_s"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
                                     "merge_layer_us": r2["merge_layer_us"], "attend_us": r2["attend_us"],
                                     "kernels": r2["kernels"]}}
+        line["also"]["kv_cache_of_" + args.workload] = run_kv_cache(args.workload, args.steps, args.warmup)
     print(json.dumps(line))
 
 

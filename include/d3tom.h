@@ -9,9 +9,10 @@
  *     d3tom_select_topk  keep the ceil(keep_ratio |V|) highest-scoring visual tokens
  *     d3tom_merge        send every other visual token to its most cosine-similar kept token,
  *                        aggregate, and physically remove the merged positions
+ *                        (d3tom_merge_kv: the same on a key/value cache, Section 4.4)
  *     d3tom_attend       full (unmasked) attention over the shortened sequence
  *
- * Conventions shared by the four device entry points
+ * Conventions shared by the device entry points
  * --------------------------------------------------
  * Pointers   Every pointer is a DEVICE pointer owned by the caller, unless the parameter is
  *            documented "host".  The library never allocates, frees or keeps a pointer.
@@ -172,6 +173,28 @@ int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
                 int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
                 const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
                 void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_merge_kv — the same merge applied to a key/value cache (Section 4.4, "Compatibility with
+ * KV-Cache": pi(m) = argmax over kept k of the cosine of the cached key rows K_m, K_k; then
+ * K_pi(m) <- K_pi(m) + K_m and V_pi(m) <- V_pi(m) + V_m, and the merged positions are dropped).
+ *
+ * The routing is computed once, on the rows of k_cache (all d = H * dh elements of a row), and
+ * both caches are aggregated with it in one pass.  mode, row order, rounding, ties and the index
+ * outputs are those of d3tom_merge; SUM is the printed update, MEAN divides both caches by the
+ * member count ("merge caches and renormalise").
+ *
+ *   k_cache, v_cache  [seq_off[B], d] dt   cached key / value rows (layout as in d3tom_merge: the
+ *                     visual block of sample b is rows vis_start[b] .. + vis_count[b])
+ *   k_out, v_out      [out_off[B], d] dt   out: the shortened caches
+ *   all other arguments as in d3tom_merge; workspace size is that of D3TOM_OP_MERGE
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
+                   int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
+                   const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
+                   int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
+                   const int32_t* out_off, void* k_out, void* v_out, int32_t* assign, int32_t* counts,
+                   int32_t* src_pos, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * d3tom_attend — bidirectional attention over the shortened sequence (Section 3.2: the shortened

@@ -183,6 +183,16 @@ def merge_layer(q, k, x, dec_idx, vis_start: int, V: int, keep_k: int, mode: str
     return dict(S=S, kept_idx=kept, slot_of=slot_of, assign=a, best_cos=bc, y=y, counts=counts, src_pos=src)
 
 
+def merge_kv(k_cache, v_cache, vis_start: int, V: int, kept_idx, mode: str = "mean") -> dict:
+    """KV-cache variant (Section 4.4): routing pi(m) from the cosine of the cached key rows, then the
+    same aggregation applied to the key cache and to the value cache, merged positions dropped."""
+    a, bc = assign(k_cache, vis_start, V, kept_idx, return_cos=True)
+    yk, counts, src = merge(k_cache, vis_start, V, kept_idx, a, mode)
+    yv, counts_v, src_v = merge(v_cache, vis_start, V, kept_idx, a, mode)
+    assert np.array_equal(counts, counts_v) and np.array_equal(src, src_v)
+    return dict(assign=a, best_cos=bc, k=yk, v=yv, counts=counts, src_pos=src)
+
+
 # cost model (Section 4.3 / Appendix B)
 def flops_layer(n, d, m): return float(lib().oracle_flops_layer(n, d, m))
 def flops_merge(alpha, V, d): return float(lib().oracle_flops_merge(alpha, V, d))

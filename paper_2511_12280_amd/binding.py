@@ -30,7 +30,7 @@ D3TOM_OP_IMPORTANCE, D3TOM_OP_SELECT_TOPK, D3TOM_OP_MERGE, D3TOM_OP_ATTEND = ran
 D3TOM_MAX_VISUAL, D3TOM_MAX_DECIDERS = 16384, 256
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
-           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_attend",
+           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
 _vp, _i, _f, _d, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_double, ctypes.c_size_t
@@ -52,6 +52,9 @@ _lib.d3tom_select_topk.argtypes = [_vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _vp, _s
 _lib.d3tom_merge.restype = _i
 _lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
                              _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.d3tom_merge_kv.restype = _i
+_lib.d3tom_merge_kv.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
+                                _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
 
@@ -217,6 +220,20 @@ def d3tom_merge(x: torch.Tensor, sim: Optional[torch.Tensor], lay: Layout, kept_
                             _ptr(assign), _ptr(counts), _ptr(src_pos), _ptr(ws), ws.numel(), _stream(stream)),
            "d3tom_merge")
     return y
+
+
+def d3tom_merge_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, lay: Layout, kept_idx: torch.Tensor, mode: int,
+                   k_out: torch.Tensor, v_out: torch.Tensor, assign: Optional[torch.Tensor],
+                   counts: Optional[torch.Tensor], src_pos: Optional[torch.Tensor], ws: torch.Tensor, stream=None):
+    """k_cache, v_cache [sum N, d]; k_out, v_out [sum N_m, d] (written); index outputs as in d3tom_merge."""
+    d = k_cache.shape[-1]
+    _check(_lib.d3tom_merge_kv(_ptr(k_cache), _ptr(v_cache), d, _dt(k_cache), lay.B, _ptr(lay.seq_off),
+                               _ptr(lay.vis_start), _ptr(lay.vis_count), _ptr(lay.vis_off), _ptr(kept_idx),
+                               _ptr(lay.kept_off), lay.max_N, lay.max_V, lay.max_keep, lay.max_pruned, lay.max_Nm,
+                               int(mode), _ptr(lay.out_off), _ptr(k_out), _ptr(v_out), _ptr(assign), _ptr(counts),
+                               _ptr(src_pos), _ptr(ws), ws.numel(), _stream(stream)),
+           "d3tom_merge_kv")
+    return k_out, v_out
 
 
 def d3tom_attend(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int,

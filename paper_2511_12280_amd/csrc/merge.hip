@@ -430,12 +430,18 @@ constexpr int SCAT_LIST = 256;     // members staged per pass
 constexpr int SCAT_WAVE = SCAT_LIST / 4;
 template <typename T, int CPT>     // CPT: 16-byte chunks per thread per pass
 __global__ __launch_bounds__(256) void merge_scatter_kernel(
-    const T* __restrict__ x, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
+    const T* __restrict__ x0, const T* __restrict__ x1, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const int32_t* __restrict__ slot_of_tok,
-    T* __restrict__ y, int32_t* __restrict__ counts, int32_t* __restrict__ src_pos) {
+    T* __restrict__ y0, T* __restrict__ y1, int32_t* __restrict__ counts_out, int32_t* __restrict__ src_pos_out) {
     constexpr int EPC = 16 / sizeof(T);
     const int o = blockIdx.x, b = blockIdx.y;
+    // blockIdx.z selects the payload (a second one shares the routing: key and value caches); the
+    // index outputs are written by the first payload's workgroups only
+    const T* __restrict__ x = blockIdx.z ? x1 : x0;
+    T* __restrict__ y = blockIdx.z ? y1 : y0;
+    int32_t* counts = blockIdx.z ? nullptr : counts_out;
+    int32_t* src_pos = blockIdx.z ? nullptr : src_pos_out;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int N_m = s.N - s.M;
     if (o >= N_m) return;
@@ -588,24 +594,27 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
 
 using namespace d3tom;
 
-extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
-                           int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
-                           const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
-                           int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
-                           const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
-                           void* ws, size_t ws_bytes, void* stream) {
-    if (!x || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off || !y)
+// Both entry points: norms + pruned list, cosine argmax, token -> slot table, scatter of one or two
+// payloads that share the routing.
+static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const void* sim, int d, int d_sim, int dt,
+                     int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
+                     const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
+                     int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
+                     const int32_t* out_off, int32_t* assign, int32_t* counts, int32_t* src_pos,
+                     void* ws, size_t ws_bytes, void* stream) {
+    if (!x0 || !y0 || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off)
         return D3TOM_ERR_INVALID_ARG;
+    if ((x1 == nullptr) != (y1 == nullptr)) return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || d < 1 || max_N < 1 || max_V < 1 || max_V > max_N || max_keep < 1 || max_keep > max_V ||
         max_pruned < 0 || max_pruned > max_V || max_out < 1 || max_out > max_N)
         return D3TOM_ERR_INVALID_ARG;
     if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
     if (mode != D3TOM_MERGE_MEAN && mode != D3TOM_MERGE_SUM) return D3TOM_ERR_INVALID_ARG;
     const int epc = (dt == D3TOM_BF16) ? 8 : 4;
-    if (!sim) { sim = x; d_sim = d; }
+    if (!sim) { sim = x0; d_sim = d; }
     if (d_sim < 1) return D3TOM_ERR_INVALID_ARG;
     if ((d % epc) || (d_sim % epc)) return D3TOM_ERR_UNSUPPORTED;
-    if (!aligned16(x) || !aligned16(sim) || !aligned16(y)) return D3TOM_ERR_INVALID_ARG;
+    if (!aligned16(x0) || !aligned16(sim) || !aligned16(y0) || !aligned16(x1) || !aligned16(y1)) return D3TOM_ERR_INVALID_ARG;
     if (max_V > D3TOM_MAX_VISUAL) return D3TOM_ERR_UNSUPPORTED;
     const MergeWs w = merge_ws_layout(B, max_V);
     if (!ws) return D3TOM_ERR_INVALID_ARG;
@@ -677,14 +686,37 @@ extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int
         seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
         assign, mem));
 
-    const dim3 gs(max_out, B);    // output rows per sample; surplus workgroups of shorter samples exit at once
+    const dim3 gs(max_out, B, x1 ? 2 : 1);    // output rows per sample (surplus workgroups of shorter samples exit at once) x payloads
     if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>(
-            (const uint16_t*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, mem,
-            (uint16_t*)y, counts, src_pos));
+            (const uint16_t*)x0, (const uint16_t*)x1, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode,
+            out_off, mem, (uint16_t*)y0, (uint16_t*)y1, counts, src_pos));
     else
         D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<float, 2><<<gs, 256, 0, st>>>(
-            (const float*)x, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode, out_off, mem,
-            (float*)y, counts, src_pos));
+            (const float*)x0, (const float*)x1, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode,
+            out_off, mem, (float*)y0, (float*)y1, counts, src_pos));
     return D3TOM_OK;
+}
+
+extern "C" int d3tom_merge(const void* x, const void* sim, int d, int d_sim, int dt,
+                           int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
+                           const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
+                           int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
+                           const int32_t* out_off, void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
+                           void* ws, size_t ws_bytes, void* stream) {
+    return merge_run(x, y, nullptr, nullptr, sim, d, d_sim, dt, B, seq_off, vis_start, vis_count, vis_off, kept_idx,
+                     kept_off, max_N, max_V, max_keep, max_pruned, max_out, mode, out_off, assign, counts, src_pos, ws,
+                     ws_bytes, stream);
+}
+
+extern "C" int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
+                              int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
+                              const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
+                              int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
+                              const int32_t* out_off, void* k_out, void* v_out, int32_t* assign, int32_t* counts,
+                              int32_t* src_pos, void* ws, size_t ws_bytes, void* stream) {
+    if (!k_cache || !v_cache || !k_out || !v_out) return D3TOM_ERR_INVALID_ARG;
+    return merge_run(k_cache, k_out, v_cache, v_out, k_cache, d, d, dt, B, seq_off, vis_start, vis_count, vis_off,
+                     kept_idx, kept_off, max_N, max_V, max_keep, max_pruned, max_out, mode, out_off, assign, counts,
+                     src_pos, ws, ws_bytes, stream);
 }

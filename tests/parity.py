@@ -71,6 +71,20 @@ class GpuStep:
         return dict(y=self.split(B.to_host(self.y), lay.Nm), assign=self.split(B.to_host(self.assign), lay.V),
                     counts=self.split(B.to_host(self.counts), lay.keep), src_pos=self.split(B.to_host(self.src_pos), lay.Nm))
 
+    def merge_kv(self, v_cache_rows: np.ndarray, kept: Optional[List[np.ndarray]] = None):
+        """KV-cache variant: the samples' `x` rows play the key cache, `v_cache_rows` [sum N, d] the value cache."""
+        if kept is not None:
+            self.kept_idx.copy_(torch.from_numpy(np.concatenate(kept).astype(np.int32)))
+        vc = B.to_device(v_cache_rows, self.dtype)
+        v_out = torch.zeros_like(self.y)
+        B.d3tom_merge_kv(self.x, vc, self.lay, self.kept_idx, self.mode, self.y, v_out, self.assign, self.counts,
+                         self.src_pos, self.ws_merge)
+        torch.cuda.synchronize()
+        lay = self.lay
+        return dict(y=self.split(B.to_host(self.y), lay.Nm), v=self.split(B.to_host(v_out), lay.Nm),
+                    assign=self.split(B.to_host(self.assign), lay.V), counts=self.split(B.to_host(self.counts), lay.keep),
+                    src_pos=self.split(B.to_host(self.src_pos), lay.Nm))
+
     @staticmethod
     def split(a: np.ndarray, sizes: Sequence[int]) -> List[np.ndarray]:
         out, o = [], 0

@@ -199,6 +199,33 @@ def test_edge_counts():
     np.testing.assert_array_equal(mout["counts"][0], [1196, 1, 1, 1, 1])
 
 
+# ---- KV-cache variant (Section 4.4): one routing from the key cache, both caches aggregated ------------
+@pytest.mark.parametrize("mode", ["mean", "sum"])
+def test_merge_kv_ragged_batch(mode):
+    shapes = [(64, 900, 0, 0.2), (20, 411, 0, 0.5), (0, 1300, 0, 0.1)]          # (prompt, visual, response, keep)
+    samples, keeps, vrows = [], [], []
+    for i, (P, V, O, keep) in enumerate(shapes):
+        c = W.random_case(500 + i, P + V + O, 4 * 128, 4, P, V, 3, dtype="bf16", centres=max(4, V // 8))
+        samples.append(c); keeps.append(oracle.keep_count(V, keep))
+        vrows.append(W.round_to(np.random.default_rng(600 + i).standard_normal(c["x"].shape).astype(np.float32), "bf16"))
+    step = GpuStep(samples, keeps, "bf16", B.D3TOM_MERGE_MEAN if mode == "mean" else B.D3TOM_MERGE_SUM)
+    rng = np.random.default_rng(7)
+    kept = [np.sort(rng.choice(s["V"], size=k, replace=False)).astype(np.int32) for s, k in zip(samples, keeps)]
+    out = step.merge_kv(np.concatenate(vrows), kept)
+    for b, s in enumerate(samples):
+        check_assign(out["assign"][b], s["x"], s["vis_start"], s["V"], kept[b])
+        # both caches against the oracle's aggregation run on the GPU's own routing
+        check_merge({"y": out["y"][b], "assign": out["assign"][b], "counts": out["counts"][b], "src_pos": out["src_pos"][b]},
+                    s["x"], s["vis_start"], s["V"], kept[b], "bf16", mode)
+        check_merge({"y": out["v"][b], "assign": out["assign"][b], "counts": out["counts"][b], "src_pos": out["src_pos"][b]},
+                    vrows[b], s["vis_start"], s["V"], kept[b], "bf16", mode)
+    # the key half equals what d3tom_merge gives for the same rows and kept set (same kernels, same routing)
+    ref = GpuStep(samples, keeps, "bf16", step.mode).merge(kept)
+    for b in range(len(samples)):
+        np.testing.assert_array_equal(ref["y"][b], out["y"][b])
+        np.testing.assert_array_equal(ref["assign"][b], out["assign"][b])
+
+
 def test_bitwise_determinism():
     c = W.random_case(41, 900, 4 * 128, 4, 30, 800, 12, dtype="bf16", centres=60)
     k = oracle.keep_count(800, 0.2)

@@ -60,3 +60,7 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu(lib):
     # null pointers are refused on the host before anything touches a device
     lib.d3tom_attend.restype = ctypes.c_int
     assert lib.d3tom_attend(None, None, None, 1, 1, None, 1, 1, 64, ctypes.c_float(1.0), None, None, ctypes.c_size_t(0), None) == 1
+    lib.d3tom_merge_kv.restype = ctypes.c_int
+    i = ctypes.c_int
+    assert lib.d3tom_merge_kv(None, None, i(64), i(1), i(1), None, None, None, None, None, None, i(8), i(4), i(2), i(2), i(6),
+                              i(0), None, None, None, None, None, None, None, ctypes.c_size_t(0), None) == 1

@@ -285,6 +285,60 @@ def test_merged_length_follows_paper_formula():
 
 
 # --------------------------------------------------------------------------------------
+# KV-cache variant (Section 4.4): routing from the cached keys, both caches aggregated with it
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+def test_merge_kv_follows_the_cache_equations(mode):
+    """Written out from the section's three equations with plain loops (pi(m), K_pi(m) += K_m,
+    V_pi(m) += V_m, drop the merged positions); a prompt block precedes the visual block as in the
+    cache the section describes."""
+    P, V, d, k = 4, 37, 16, 6
+    r = _rng(44)
+    K = W.round_to(r.standard_normal((P + V, d)).astype(np.float32), "bf16")
+    Vc = W.round_to(r.standard_normal((P + V, d)).astype(np.float32), "bf16")
+    kept = np.sort(r.choice(V, size=k, replace=False)).astype(np.int32)
+    out = oracle.merge_kv(K, Vc, P, V, kept, mode)
+    Kd, Vd = K.astype(np.float64), Vc.astype(np.float64)
+    Ksum = {int(j): Kd[P + j].copy() for j in kept}
+    Vsum = {int(j): Vd[P + j].copy() for j in kept}
+    cnt = {int(j): 1 for j in kept}
+    for m in range(V):
+        if m in cnt:
+            continue
+        best, arg = -np.inf, None
+        for j in kept:                                   # ascending: the first strict maximum wins
+            c = float(Kd[P + m] @ Kd[P + j]) / (np.linalg.norm(Kd[P + m]) * np.linalg.norm(Kd[P + j]))
+            if c > best:
+                best, arg = c, int(j)
+        Ksum[arg] += Kd[P + m]; Vsum[arg] += Vd[P + m]; cnt[arg] += 1
+    for slot, j in enumerate(kept):
+        div = cnt[int(j)] if mode == "mean" else 1
+        np.testing.assert_allclose(out["k"][P + slot], Ksum[int(j)] / div, rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(out["v"][P + slot], Vsum[int(j)] / div, rtol=1e-12, atol=1e-12)
+        assert out["counts"][slot] == cnt[int(j)]
+    assert out["k"].shape == (P + k, d) and out["v"].shape == (P + k, d)          # L_kept rows
+    np.testing.assert_array_equal(out["k"][:P], Kd[:P])
+    np.testing.assert_array_equal(out["v"][:P], Vd[:P])
+
+
+def test_merge_kv_routing_ignores_the_value_cache():
+    P, V, d, k = 0, 50, 8, 7
+    c = W.random_case(45, V, d, 1, P, V, 2, centres=5)
+    K = c["x"]
+    r = _rng(46)
+    V1 = r.standard_normal((V, d)).astype(np.float32)
+    V2 = (3.0 * r.standard_normal((V, d))).astype(np.float32)
+    kept = np.sort(r.choice(V, size=k, replace=False)).astype(np.int32)
+    a = oracle.merge_kv(K, V1, P, V, kept, "sum")
+    b = oracle.merge_kv(K, V2, P, V, kept, "sum")
+    np.testing.assert_array_equal(a["assign"], b["assign"])
+    np.testing.assert_array_equal(a["k"], b["k"])
+    # mass of both caches is conserved by the plain sums
+    np.testing.assert_allclose(a["v"].sum(axis=0), V1.astype(np.float64).sum(axis=0), rtol=1e-10, atol=1e-10)
+    np.testing.assert_allclose(b["v"].sum(axis=0), V2.astype(np.float64).sum(axis=0), rtol=1e-10, atol=1e-10)
+
+
+# --------------------------------------------------------------------------------------
 # attention (bidirectional, no mask)
 # --------------------------------------------------------------------------------------
 @pytest.mark.parametrize("n,H,dh", [(1, 1, 4), (17, 2, 8), (70, 3, 16)])
