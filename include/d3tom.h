@@ -11,6 +11,7 @@
  *                        aggregate, and physically remove the merged positions
  *                        (d3tom_merge_kv: the same on a key/value cache, Section 4.4)
  *     d3tom_attend       full (unmasked) attention over the shortened sequence
+ * and, between steps, d3tom_update_deciders builds the decider set of the next step on the device.
  *
  * Conventions shared by the device entry points
  * --------------------------------------------------
@@ -212,6 +213,28 @@ int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
 int d3tom_attend(const void* q, const void* k, const void* v, int dt,
                  int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
                  void* o, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_update_deciders — the decider set for the next merge (Section 3.1, "The Decider-Guided
+ * Mechanism": D = { positions that hold a token now and held [MASK] in the preceding iteration };
+ * Algorithm 1, the last line of the denoising loop; an empty set means "run this step unmerged").
+ *
+ *   prev_ids, cur_ids  int32[seq_off[B]]  token ids of every position one iteration ago / now
+ *                      (prompt and visual positions never hold mask_id, so they never qualify)
+ *   mask_id            id of the [MASK] token
+ *   max_D              host-known cap per sample, 1 .. D3TOM_MAX_DECIDERS; a sample with more newly
+ *                      revealed positions lists the max_D lowest ones (dec_count still reports all)
+ *   dec_idx            int32[B * max_D]  out: decider positions within each sample, ascending, packed
+ *   dec_off            int32[B + 1]      out: offsets into dec_idx (prefix sums of the listed counts)
+ *   dec_count          int32[B] out or NULL: number of newly revealed positions per sample
+ *
+ * dec_idx / dec_off are exactly what d3tom_importance takes.  Its min_D / max_D arguments are host
+ * values: a caller that cannot bound them otherwise copies dec_count (4 B bytes) back once per
+ * step; a sample with dec_count 0 must skip the merge (D3TOM_ERR_NO_DECIDERS mirrors that case).
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_update_deciders(const int32_t* prev_ids, const int32_t* cur_ids, int mask_id,
+                          int B, const int32_t* seq_off, int max_D,
+                          int32_t* dec_idx, int32_t* dec_off, int32_t* dec_count, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * Per-kernel timing (diagnostics; used by the benchmark for its roofline figures).  While enabled,

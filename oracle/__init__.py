@@ -43,6 +43,8 @@ def lib():
         L.oracle_threads.restype = ctypes.c_int
         L.oracle_keep_count.restype = ctypes.c_int
         L.oracle_keep_count.argtypes = [ctypes.c_int, ctypes.c_double]
+        L.oracle_deciders.restype = ctypes.c_int
+        L.oracle_deciders.argtypes = [_i32p, _i32p, ctypes.c_int, ctypes.c_int, _i32p, ctypes.c_int]
         L.oracle_schedule.restype = ctypes.c_double
         L.oracle_schedule.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_double, ctypes.c_double]
         L.oracle_importance.argtypes = [_f32p, _f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
@@ -97,6 +99,15 @@ def keep_count(V: int, keep_ratio: float) -> int:
 
 def schedule(step: int, T: int, r_first: float, r_last: float) -> float:
     return float(lib().oracle_schedule(int(step), int(T), float(r_first), float(r_last)))
+
+
+def deciders(prev_ids, cur_ids, mask_id: int) -> np.ndarray:
+    """Ascending positions that hold a token now and held [MASK] one iteration earlier."""
+    p = _i32(prev_ids); c = _i32(cur_ids)
+    assert p.shape == c.shape and p.ndim == 1
+    out = np.zeros(max(len(p), 1), dtype=np.int32)
+    n = lib().oracle_deciders(_p(p, _i32p), _p(c, _i32p), len(p), int(mask_id), _p(out, _i32p), len(out))
+    return out[:n].copy()
 
 
 def importance(q, k, dec_idx, vis_start: int, V: int, scale: Optional[float] = None,

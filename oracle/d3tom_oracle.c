@@ -45,6 +45,21 @@ int oracle_keep_count(int V, double keep_ratio) {
     return (int)c;
 }
 
+/* Decider set (Section 3.1, "The Decider-Guided Mechanism"): the positions that
+ * hold a token in the current iterate and held [MASK] in the preceding one,
+ * listed in ascending position.  Returns their number; at most `cap` are
+ * written to out. */
+int oracle_deciders(const int32_t* prev_ids, const int32_t* cur_ids, int n, int mask_id, int32_t* out, int cap) {
+    int c = 0;
+    for (int i = 0; i < n; ++i) {
+        if (cur_ids[i] != mask_id && prev_ids[i] == mask_id) {
+            if (c < cap) out[c] = i;
+            ++c;
+        }
+    }
+    return c;
+}
+
 /* Linear schedule of Section 3.2 ("Timestep-Dependent Merge Schedule"),
  * written direction-neutrally: value at decoding-order step s of T, moving
  * linearly from r_first (s = 0) to r_last (s = T-1). */

@@ -30,7 +30,7 @@ D3TOM_OP_IMPORTANCE, D3TOM_OP_SELECT_TOPK, D3TOM_OP_MERGE, D3TOM_OP_ATTEND = ran
 D3TOM_MAX_VISUAL, D3TOM_MAX_DECIDERS = 16384, 256
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
-           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend",
+           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_update_deciders",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
 _vp, _i, _f, _d, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_double, ctypes.c_size_t
@@ -55,6 +55,8 @@ _lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, 
 _lib.d3tom_merge_kv.restype = _i
 _lib.d3tom_merge_kv.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
                                 _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.d3tom_update_deciders.restype = _i
+_lib.d3tom_update_deciders.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
 
@@ -245,6 +247,18 @@ def d3tom_attend(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: 
                              float(scale), _ptr(o), _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream)),
            "d3tom_attend")
     return o
+
+
+def d3tom_update_deciders(prev_ids: torch.Tensor, cur_ids: torch.Tensor, mask_id: int, seq_off: torch.Tensor, max_D: int,
+                          dec_idx: torch.Tensor, dec_off: torch.Tensor, dec_count: Optional[torch.Tensor] = None,
+                          stream=None):
+    """prev_ids, cur_ids int32 [sum N]; dec_idx int32 [B * max_D], dec_off int32 [B + 1], dec_count int32 [B] (written)."""
+    Bn = seq_off.numel() - 1
+    assert dec_idx.numel() >= Bn * max_D and dec_off.numel() >= Bn + 1
+    _check(_lib.d3tom_update_deciders(_ptr(prev_ids), _ptr(cur_ids), int(mask_id), Bn, _ptr(seq_off), int(max_D),
+                                      _ptr(dec_idx), _ptr(dec_off), _ptr(dec_count), _stream(stream)),
+           "d3tom_update_deciders")
+    return dec_idx, dec_off
 
 
 # ---- tensor <-> numpy helpers for the storage types (bit moves only) ---------------------------------

@@ -242,3 +242,25 @@ def random_qkv(seed: int, n: int, H: int, dh: int, dtype: str = "f32", spread: f
     rng = np.random.default_rng([seed, 9])
     return tuple(round_to(np.float32(spread) * rng.standard_normal((n, H, dh), dtype=np.float32), dtype)
                  for _ in range(3))
+
+
+def mask_trajectory(seed: int, n_prefix: int, n_response: int, steps: int, mask_id: int = 126336, vocab: int = 32000):
+    """Token-id states of one sample over a denoising run: `steps + 1` int32 arrays of length
+    n_prefix + n_response.  The prefix (visual + prompt positions) always holds ordinary ids; the response
+    starts fully masked and a random subset of the still-masked positions is revealed at every step (all
+    of them by the last one).  Which positions are revealed when is the only thing drawn here."""
+    rng = np.random.default_rng(seed)
+    ids = rng.integers(0, vocab, size=n_prefix + n_response).astype(np.int32)
+    order = rng.permutation(n_response)
+    cuts = np.sort(rng.choice(np.arange(1, n_response), size=min(steps - 1, n_response - 1), replace=False)) \
+        if n_response > 1 and steps > 1 else np.array([], dtype=np.int64)
+    bounds = np.concatenate([[0], cuts, [n_response]]).astype(np.int64)
+    state = ids.copy()
+    state[n_prefix:] = mask_id
+    states = [state.copy()]
+    for a, b in zip(bounds[:-1], bounds[1:]):
+        pos = n_prefix + order[a:b]
+        state[pos] = ids[pos]
+        states.append(state.copy())
+    return states
+

@@ -226,6 +226,46 @@ def test_merge_kv_ragged_batch(mode):
         np.testing.assert_array_equal(ref["assign"][b], out["assign"][b])
 
 
+# ---- decider bookkeeping on the device (Section 3.1) ----------------------------------------------------
+def test_update_deciders_batch_and_chain_into_importance():
+    M = 126336
+    specs = [(300, 64, 9), (1152 - 64, 64, 5), (0, 1500, 4), (2688 - 256, 256, 2), (10, 1, 1)]     # (prefix, response, steps)
+    trajs = [W.mask_trajectory(70 + i, p, r, t, mask_id=M) for i, (p, r, t) in enumerate(specs)]
+    lens = [p + r for p, r, _ in specs]
+    seq_off = torch.from_numpy(np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)).cuda()
+    nb = len(specs)
+    for max_D, pick in ((256, 1), (16, 1), (256, 0)):       # pick: which transition of each trajectory (0 = the first)
+        prev = np.concatenate([t[min(pick, len(t) - 2)] for t in trajs])
+        cur = np.concatenate([t[min(pick, len(t) - 2) + 1] for t in trajs])
+        dec_idx = torch.full((nb * max_D,), -7, dtype=torch.int32, device="cuda")
+        dec_off = torch.full((nb + 1,), -7, dtype=torch.int32, device="cuda")
+        dec_cnt = torch.full((nb,), -7, dtype=torch.int32, device="cuda")
+        B.d3tom_update_deciders(torch.from_numpy(prev).cuda(), torch.from_numpy(cur).cuda(), M, seq_off, max_D,
+                                dec_idx, dec_off, dec_cnt)
+        torch.cuda.synchronize()
+        off, cnt, idx = dec_off.cpu().numpy(), dec_cnt.cpu().numpy(), dec_idx.cpu().numpy()
+        o = 0
+        for b in range(nb):
+            a0 = sum(lens[:b])
+            ref = oracle.deciders(prev[a0:a0 + lens[b]], cur[a0:a0 + lens[b]], M)
+            assert cnt[b] == len(ref) and off[b] == o
+            np.testing.assert_array_equal(idx[o:o + min(len(ref), max_D)], ref[:max_D])
+            o += min(len(ref), max_D)
+        assert off[nb] == o
+    # the device-built list feeds d3tom_importance directly and gives the scores of the host-built one
+    c = W.random_case(90, 700, 4 * 128, 4, 30, 600, 12, dtype="bf16", centres=40)
+    c["dec_idx"] = np.sort(c["dec_idx"])
+    step = GpuStep([c], [60], "bf16")
+    S_ref = step.importance()[0].copy()
+    prev = np.full(700, 7, np.int32); cur = prev.copy()
+    prev[c["dec_idx"]] = M
+    so = torch.tensor([0, 700], dtype=torch.int32, device="cuda")
+    step.lay.dec_idx.zero_()
+    B.d3tom_update_deciders(torch.from_numpy(prev).cuda(), torch.from_numpy(cur).cuda(), M, so, 12,
+                            step.lay.dec_idx, step.lay.dec_off, None)
+    np.testing.assert_array_equal(step.importance()[0], S_ref)
+
+
 def test_bitwise_determinism():
     c = W.random_case(41, 900, 4 * 128, 4, 30, 800, 12, dtype="bf16", centres=60)
     k = oracle.keep_count(800, 0.2)

@@ -64,3 +64,17 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu(lib):
     i = ctypes.c_int
     assert lib.d3tom_merge_kv(None, None, i(64), i(1), i(1), None, None, None, None, None, None, i(8), i(4), i(2), i(2), i(6),
                               i(0), None, None, None, None, None, None, None, ctypes.c_size_t(0), None) == 1
+
+
+def test_schedule_variants_share_their_mean(lib):
+    from paper_2511_12280_amd import binding as B
+    # low -> high (D3ToM-t) and its reverse (D3ToM-t dagger) through the one direction-neutral helper:
+    # both are linear between the same two ends, so their mean over the T steps is the midpoint
+    # (the calibration the schedule ablation in the appendix states), and they mirror each other
+    T, lo, hi = 32, 0.5, 0.9
+    fwd = [B.d3tom_schedule(s, T, lo, hi) for s in range(T)]
+    rev = [B.d3tom_schedule(s, T, hi, lo) for s in range(T)]
+    assert fwd[0] == lo and fwd[-1] == pytest.approx(hi) and all(b > a for a, b in zip(fwd, fwd[1:]))
+    assert sum(fwd) / T == pytest.approx((lo + hi) / 2) and sum(rev) / T == pytest.approx((lo + hi) / 2)
+    assert rev == pytest.approx(fwd[::-1])
+

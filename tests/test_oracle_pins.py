@@ -404,3 +404,34 @@ def test_cost_model_merge_overhead_term():
     # 2 a (1-a) |V|^2 d + a |V| d: similarity matrix (pruned x kept x d, 2 flops each) + one add per merged element
     V, d, a = 1000.0, 4096.0, 0.9
     assert oracle.flops_merge(a, V, d) == pytest.approx(2 * (a * V) * ((1 - a) * V) * d + a * V * d)
+
+
+# --------------------------------------------------------------------------------------
+# decider bookkeeping (Section 3.1; Algorithm 1, the update after every step)
+# --------------------------------------------------------------------------------------
+def test_deciders_definition_on_a_written_out_example():
+    M = 9
+    prev = [5, 5, M, M, M, 7, M]
+    cur = [5, 5, 3, M, 4, 7, M]          # positions 2 and 4 were revealed; 0, 1, 5 were never masked; 3, 6 still masked
+    np.testing.assert_array_equal(oracle.deciders(prev, cur, M), [2, 4])
+    np.testing.assert_array_equal(oracle.deciders(prev, prev, M), [])                 # nothing revealed: empty set
+    np.testing.assert_array_equal(oracle.deciders([M] * 4, [1, 2, 3, 4], M), [0, 1, 2, 3])
+    np.testing.assert_array_equal(oracle.deciders(cur, prev, M), [])                  # re-masking never makes a decider
+
+
+def test_deciders_over_a_whole_trajectory_partition_the_response():
+    """Initially everything is masked and the first set is empty (Algorithm 1, Init); afterwards every
+    response position is a decider exactly once, at the step right after it is revealed."""
+    M, n_prefix, n_resp, T = 126336, 40, 64, 12
+    states = W.mask_trajectory(3, n_prefix, n_resp, T, mask_id=M)
+    assert (states[0][n_prefix:] == M).all() and (states[-1] != M).all()
+    seen = np.zeros(n_prefix + n_resp, dtype=int)
+    for prev, cur in zip(states[:-1], states[1:]):
+        d = oracle.deciders(prev, cur, M)
+        brute = [i for i in range(len(cur)) if cur[i] != M and prev[i] == M]
+        np.testing.assert_array_equal(d, brute)
+        assert len(d) >= 1 and (d >= n_prefix).all() and (np.diff(d) > 0).all()
+        seen[d] += 1
+    np.testing.assert_array_equal(seen[:n_prefix], 0)
+    np.testing.assert_array_equal(seen[n_prefix:], 1)
+
