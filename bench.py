@@ -111,7 +111,7 @@ def algorithmic(wl, lay):
         out["imp_scores"][0] += (V + D) * d * eb + 4 * V;   out["imp_scores"][1] += 2.0 * D * V * d
         out["imp_finish"][0] += 4 * V * (wl.H + 1)
         out["topk_select"][0] += 4 * V + 4 * k + 4 * V
-        out["merge_norms"][0] += V * d * eb + 4 * V
+        out["merge_norms"][0] += k * d * eb + 4 * k
         out["cos_argmax"][0] += V * d * eb;                 out["cos_argmax"][1] += 2.0 * M * k * d
         out["merge_assign"][0] += 8 * M * max(1, -(-k // 128)) + 8 * V
         out["merge_scatter"][0] += (N + Nm) * d * eb + 4 * V
@@ -145,7 +145,8 @@ def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
     for i in range(steps):
         a = algorithmic(wl, dev[i % len(dev)]["lay"])
         for k in alg:
-            alg[k][0] += a[k][0]; alg[k][1] += a[k][1]
+            by, fl = a.get(k, (0.0, 0.0))
+            alg[k][0] += by; alg[k][1] += fl
     kernels = {}
     for k, (ms, calls) in prof.items():
         if calls == 0:

@@ -2,8 +2,9 @@
 // FORALL block and the "Remove positions" line).
 //
 // Stages, all on the caller's stream:
-//   norms     1 / ||row|| of every visual row of the similarity features (1 wave / row); one extra
-//             workgroup per sample turns kept_idx into the ascending list of pruned visual tokens
+//   norms     1 / ||row|| of every KEPT row of the similarity features (1 wave / row): the argmax over
+//             kept slots of dot / (|m| |k|) does not depend on |m|, the pruned row's own norm; the same
+//             waves write the ascending list of pruned visual tokens (the gaps of the ascending kept_idx)
 //   cosine    pruned x kept similarity GEMM on MFMA 32x32x16 bf16 with the argmax fused into the
 //             epilogue: only (best value, best slot) per (pruned row, 128-slot column tile) ever
 //             leaves the registers; the M x k matrix is never written
@@ -53,48 +54,11 @@ __device__ __forceinline__ SampleGeom sample_geom(int b, const int32_t* seq_off,
 }
 
 // ---- norms + pruned list ------------------------------------------------------------------------
-// One wave per visual row computes 1 / ||row||.  The LAST workgroup of each sample instead builds the
-// ascending list of pruned visual tokens (the complement of kept_idx) from a bitmask in LDS; it runs
-// beside the norm workgroups, so the list costs no launch of its own.
-__device__ __forceinline__ void build_pruned_list(const SampleGeom& s, const int32_t* __restrict__ kp,
-                                                  int32_t* __restrict__ out) {
-    __shared__ uint32_t bits[D3TOM_MAX_VISUAL / 32];
-    __shared__ int wtot[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nw = (s.V + 31) >> 5;
-    for (int w = tid; w < nw; w += 256) bits[w] = 0u;
-    __syncthreads();
-    for (int r = tid; r < s.k; r += 256) {
-        const int j = min(max(kp[r], 0), s.V - 1);
-        atomicOr(&bits[j >> 5], 1u << (j & 31));
-    }
-    __syncthreads();
-    // thread t owns words [t*per, (t+1)*per): count its pruned tokens, scan, emit
-    const int per = (nw + 255) / 256;
-    const int w0 = min(tid * per, nw), w1 = min(w0 + per, nw);
-    int n = 0;
-    for (int w = w0; w < w1; ++w) {
-        uint32_t inv = ~bits[w];
-        if (w == nw - 1 && (s.V & 31)) inv &= (1u << (s.V & 31)) - 1u;
-        n += __popc(inv);
-    }
-    int inc = n;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int t = __shfl_up(inc, o, WAVE);
-        if (lane >= o) inc += t;
-    }
-    if (lane == 63) wtot[wave] = inc;
-    __syncthreads();
-    int p = inc - n;
-    for (int w = 0; w < wave; ++w) p += wtot[w];
-    for (int w = w0; w < w1; ++w) {
-        uint32_t inv = ~bits[w];
-        if (w == nw - 1 && (s.V & 31)) inv &= (1u << (s.V & 31)) - 1u;
-        while (inv) { const int b = __ffs((int)inv) - 1; out[p++] = w * 32 + b; inv &= inv - 1u; }
-    }
-}
-
+// One wave per kept slot r computes 1 / ||row|| of that slot's token.  The same wave also writes the
+// piece of the ascending pruned list that lies in front of its token: kept_idx is ascending, so the
+// pruned tokens j between kept_idx[r-1] and kept_idx[r] have exactly r kept tokens before them and sit
+// at positions j - r of the list (the wave of the last slot also writes the piece behind its token).
+// No scan, no extra workgroup.
 template <typename T>
 __global__ __launch_bounds__(256) void merge_norms_kernel(
     const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
@@ -102,13 +66,20 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
     int max_V, int max_keep, float* __restrict__ rnorm, int32_t* __restrict__ pruned) {
     const int b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
-    if (blockIdx.x == gridDim.x - 1) {
-        if (s.V > 0) build_pruned_list(s, kept_idx + kept_off[b], pruned + (size_t)b * max_V);
-        return;
-    }
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int r = blockIdx.x * 4 + (threadIdx.x >> 6);      // kept slot
     const int lane = threadIdx.x & 63;
-    if (j >= s.V) return;
+    if (r >= s.k) return;
+    const int32_t* kp = kept_idx + kept_off[b];
+    const int j = min(max(kp[r], 0), s.V - 1);
+    {
+        int32_t* pr = pruned + (size_t)b * max_V;
+        const int lo = (r == 0) ? -1 : min(max(kp[r - 1], 0), s.V - 1);
+        // positions are >= 0 whenever kept_idx is ascending and free of repeats; the guard only keeps an
+        // invalid list from writing in front of the array
+        for (int t = lo + 1 + lane; t < j; t += 64) if (t >= r) pr[t - r] = t;
+        if (r == s.k - 1)
+            for (int t = j + 1 + lane; t < s.V; t += 64) if (t >= s.k) pr[t - s.k] = t;
+    }
     const T* row = f + (size_t)(s.tok0 + s.vs + j) * d;
     constexpr int EPC = 16 / sizeof(T);       // elements per 16-byte chunk
     float ss = 0.f;
@@ -124,7 +95,7 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
         }
     }
     ss = wave_sum(ss);
-    if (lane == 0) rnorm[(size_t)b * max_V + j] = 1.0f / fmaxf(sqrtf(ss), 1e-15f);
+    if (lane == 0) rnorm[(size_t)b * max_V + r] = 1.0f / fmaxf(sqrtf(ss), 1e-15f);
 }
 
 // ---- cosine GEMM + fused argmax, bf16 MFMA ---------------------------------------------------
@@ -182,7 +153,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     constexpr int B_LD = COS_BN / 32;
     constexpr int LPS = A_LD + B_LD;                    // loads per wave and stage
     extern __shared__ __attribute__((aligned(16))) char ring[];
-    __shared__ float rnA[BM], rnB[COS_BN];
+    __shared__ float rnB[COS_BN];
 
     const int per = 8 * R * C;
     const int b = blockIdx.x / per;
@@ -208,7 +179,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         const int row = wave * (BM / 4) + i * 8 + (lane >> 3);
         const int cg = (lane & 7) ^ ((row >> 1) & 7);
         const int p = rt * BM + row;
-        const int m = (p < s.M) ? pr[p] : pr[0];
+        const int m = min(max((p < s.M) ? pr[p] : pr[0], 0), s.V - 1);
         a_off[i] = m * d * 2 + cg * 16;
     }
 #pragma unroll
@@ -219,10 +190,9 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         const int j = min(max(kp[(r < s.k) ? r : 0], 0), s.V - 1);
         b_off[i] = j * d * 2 + cg * 16;
     }
-    for (int t = tid; t < BM; t += 256) { const int p = rt * BM + t; rnA[t] = (p < s.M) ? rn[pr[p]] : 0.f; }
     for (int t = tid; t < COS_BN; t += 256) {
         const int r = ct * COS_BN + t;
-        rnB[t] = (r < s.k) ? rn[min(max(kp[r], 0), s.V - 1)] : 0.f;
+        rnB[t] = (r < s.k) ? rn[r] : 0.f;
     }
     auto issue = [&](int kt, int stage) {
         char* sb = ring + stage * STAGE;
@@ -293,7 +263,8 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         stage(kt, false);
     }
 
-    // epilogue: cosine = dot * rn_row * rn_col; per row, best (value, slot) over this tile's columns.
+    // epilogue: dot * rn_col (the cosine up to the row's own positive norm, which is the same for all of
+    // its candidates); per row, best (value, slot) over this tile's columns.
     // Branch-free selects, and all rows advance through each exchange step together, so the 32
     // independent cross-lane exchanges of a step are in flight at once.
     float bv[TM][16];
@@ -303,11 +274,10 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-            const float rr = rnA[row];
             const int col0 = wn * 64 + c, col1 = col0 + 32;
             const int s0 = ct * COS_BN + col0, s1 = s0 + 32;
-            const float v0 = (s0 < s.k) ? acc[i][0][e] * rr * rnB[col0] : -INFINITY;
-            const float v1 = (s1 < s.k) ? acc[i][1][e] * rr * rnB[col1] : -INFINITY;
+            const float v0 = (s0 < s.k) ? acc[i][0][e] * rnB[col0] : -INFINITY;
+            const float v1 = (s1 < s.k) ? acc[i][1][e] * rnB[col1] : -INFINITY;
             const bool t1 = v1 > v0;                       // equal values: the lower slot stays
             bv[i][e] = t1 ? v1 : v0;
             bi[i][e] = t1 ? s1 : s0;
@@ -358,7 +328,7 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
     if (p >= s.M) return;
     __shared__ float2 red[4];
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int m = pruned[(size_t)b * max_V + p];
+    const int m = min(max(pruned[(size_t)b * max_V + p], 0), s.V - 1);
     const int32_t* kp = kept_idx + kept_off[b];
     const float* rn = rnorm + (size_t)b * max_V;
     const T* xm = f + (size_t)(s.tok0 + s.vs + m) * d;
@@ -369,7 +339,7 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
         float dot = 0.f;
         for (int cidx = lane; cidx < d; cidx += 64) dot += Elem<T>::load(xm + cidx) * Elem<T>::load(xk + cidx);
         dot = wave_sum(dot);
-        const float v = dot * rn[m] * rn[j];
+        const float v = dot * rn[r];        // the pruned row's own norm scales all its candidates alike
         if (v > bv) { bv = v; bi = r; }
     }
     if (lane == 0) red[wave] = make_float2(bv, __int_as_float(bi));
@@ -636,7 +606,7 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         attr_set = true;
     }
 
-    const dim3 gn(ceil_div(max_V, 4) + 1, B);          // + 1: the workgroup that builds the pruned list
+    const dim3 gn(ceil_div(max_keep, 4), B);
     if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>(
             (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned));
