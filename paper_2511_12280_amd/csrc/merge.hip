@@ -101,7 +101,7 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 // ---- cosine GEMM + fused argmax, bf16 MFMA ---------------------------------------------------
 // Workgroup tile: (TM*64) pruned rows x 128 kept slots, 4 waves as 2 x 2, wave tile (TM*32) x 64.
 //
-// Operand tiles go HBM/L2 -> LDS with direct loads (global_load_lds, 16 bytes per lane, no register
+// Operand tiles go HBM/L2 -> LDS with direct loads (buffer_load ... lds, 16 bytes per lane, no register
 // staging) into a ring of COS_NS stages of 64 contraction elements; the loads of stage kt+3 are in
 // flight while stage kt feeds the MFMAs, one s_barrier per stage.  A wave-load writes 1 KB of LDS
 // contiguously (8 rows x 128 B), so rows cannot be padded; instead the 16-byte chunk that lands in
