@@ -23,8 +23,10 @@ namespace d3tom {
 constexpr int COS_BN = 128;        // kept slots per column tile
 constexpr int COS_BK = 64;         // contraction elements per LDS stage
 
+// split-K partial products: at most COS_SPLIT_BLOCKS (tile, k-slice) blocks of 64 x 128 floats
+constexpr int COS_SPLIT_BLOCKS = 256;
 struct MergeWs {
-    size_t pruned_off, rnorm_off, part_off, mem_off, total;
+    size_t pruned_off, rnorm_off, part_off, mem_off, dots_off, total;
     int NCT;
 };
 __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
@@ -35,6 +37,7 @@ __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
     w.rnorm_off = o;  o += align_up((size_t)B * max_V * 4, 256);
     w.part_off = o;   o += align_up((size_t)B * w.NCT * max_V * 8, 256);
     w.mem_off = o;    o += align_up((size_t)B * align_up((size_t)max_V, 4) * 4, 256);   // token -> slot table, rows of 4-entry groups
+    w.dots_off = o;   o += (size_t)COS_SPLIT_BLOCKS * 64 * 128 * sizeof(float);
     w.total = o;
     return w;
 }
@@ -145,7 +148,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
-    float2* __restrict__ part, int XC, int R, int C) {
+    float2* __restrict__ part, int XC, int R, int C, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BM = TM * 64;
     constexpr int STAGE = (BM + COS_BN) * 128;          // bytes per ring stage (64 bf16 = 128 B per row)
@@ -194,16 +197,19 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         const int r = ct * COS_BN + t;
         rnB[t] = (r < s.k) ? rn[r] : 0.f;
     }
+    // split-K: slice blockIdx.y of the contraction (ksplit slices of nkt stages each)
+    const int nkt = (d / COS_BK) / ksplit;
+    const int kt0 = (int)blockIdx.y * nkt;
     auto issue = [&](int kt, int stage) {
         char* sb = ring + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(sb + (wave * (BM / 4) + i * 8) * 128), 16,
-                                                     a_off[i], kt * (COS_BK * 2), 0, 0);
+                                                     a_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(sb + BM * 128 + (wave * (COS_BN / 4) + i * 8) * 128), 16,
-                                                     b_off[i], kt * (COS_BK * 2), 0, 0);
+                                                     b_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
     };
 
     f32x16 acc[TM][2];
@@ -221,7 +227,6 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
     for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
 
-    const int nkt = d / COS_BK;
     // one stage: (optionally) start the loads of the stage COS_NS-1 ahead, then feed stage kt to the MFMAs
     auto stage = [&](int kt, const bool prefetch) {
         if (prefetch) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
@@ -263,6 +268,22 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         stage(kt, false);
     }
 
+    if (ksplit > 1) {
+        // partial products of this k-slice: block (slice, tile) of BM x 128 floats, summed by cos_reduce_argmax
+        const int tile_id = (b * nrt_launch + rt) * nct_launch + ct;
+        const int n_tiles = (int)(gridDim.x / (8 * R * C)) * nrt_launch * nct_launch;
+        float* blk = dots + ((size_t)blockIdx.y * n_tiles + tile_id) * (BM * COS_BN);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                    blk[row * COS_BN + wn * 64 + j * 32 + c] = acc[i][j][e];
+                }
+        return;
+    }
     // epilogue: dot * rn_col (the cosine up to the row's own positive norm, which is the same for all of
     // its candidates); per row, best (value, slot) over this tile's columns.
     // Branch-free selects, and all rows advance through each exchange step together, so the 32
@@ -314,6 +335,76 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         if (half == 0 && p < s.M) part[((size_t)b * NCT + ct) * max_V + p] = make_float2(best, __int_as_float(bidx));
     }
 #endif
+}
+
+// ---- split-K second step: sum the k-slices, scale by the kept row's 1/norm, argmax over all slots ----
+// Used when the similarity matrix has too few tiles to occupy the chip (short sequences): the GEMM is
+// then cut along the contraction instead, and one wave per pruned row finishes the job here.  Slices
+// are added in ascending order and slots are visited in ascending order, so the result is deterministic
+// and ties go to the lowest slot.  The wave writes the token -> slot table entry (and `assign`) itself, and
+// waves M .. V-1 enter the kept tokens, so this launch also stands in for merge_assign_kernel.
+__global__ __launch_bounds__(256) void cos_reduce_argmax(
+    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
+    const int32_t* __restrict__ vis_off, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
+    const float* __restrict__ dots, int ksplit, int n_tiles, int nrt_launch, int nct_launch,
+    int32_t* __restrict__ assign_out, int32_t* __restrict__ slot_of_tok) {
+    constexpr int BM = 64;
+    const int b = blockIdx.y;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int p = blockIdx.x * 4 + wave;
+    if (s.k <= 0 || p >= s.V) return;
+    int32_t* table = slot_of_tok + (size_t)b * align_up((size_t)max_V, 4);
+    if (p >= s.M) {                                        // kept slot p - M: its own token
+        if (lane == 0) {
+            const int tok = min(max(kept_idx[kept_off[b] + p - s.M], 0), s.V - 1);
+            table[tok] = p - s.M;
+            if (assign_out) assign_out[vis_off[b] + tok] = p - s.M;
+        }
+        return;
+    }
+    const float* rn = rnorm + (size_t)b * max_V;
+    const int rt = p / BM, lr = p % BM;
+    const int nct = (s.k + COS_BN - 1) / COS_BN;
+    float best = -INFINITY; int bidx = 0x7FFFFFFF;
+    for (int ct = 0; ct < nct; ++ct) {
+        const int tile_id = (b * nrt_launch + rt) * nct_launch + ct;
+        // all slices of both column halves are requested before the first add (at most 16 slices)
+        float v[2][16];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int col = half * 64 + lane;
+            const bool ok = ct * COS_BN + col < s.k;
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks)
+                v[half][ks] = (ok && ks < ksplit) ? dots[((size_t)ks * n_tiles + tile_id) * (BM * COS_BN) + lr * COS_BN + col] : 0.f;
+        }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int slot = ct * COS_BN + half * 64 + lane;
+            if (slot < s.k) {
+                float sum = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 16; ++ks) sum += v[half][ks];        // ascending slices; absent ones add 0
+                const float val = sum * rn[slot];
+                if (val > best) { best = val; bidx = slot; }
+            }
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(best, o, WAVE);
+        const int oi = __shfl_xor(bidx, o, WAVE);
+        const bool take = (ov > best) | ((ov == best) & (oi < bidx));
+        best = take ? ov : best; bidx = take ? oi : bidx;
+    }
+    if (lane == 0) {
+        const int slot = min(max(bidx, 0), s.k - 1);
+        const int tok = min(max(pruned[(size_t)b * max_V + p], 0), s.V - 1);
+        table[tok] = slot;
+        if (assign_out) assign_out[vis_off[b] + tok] = slot;
+    }
 }
 
 // ---- cosine + argmax, generic: one workgroup per pruned row, waves stride over the kept slots ---
@@ -614,11 +705,23 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<float><<<gn, 256, 0, st>>>(
             (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned));
 
+    bool split = false;
     const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0) && ((size_t)max_V * d_sim * 2 < ((size_t)1 << 31));
     if (mfma) {
         const int nct = ceil_div(max_keep, COS_BN);
         // 128-row tiles unless that leaves most of the 256 CUs idle
         const int TM = ((long)nct * ceil_div(max_pruned, 128) * B >= 96) ? 2 : 1;
+        // too few 64 x 128 tiles for 256 CUs (short sequences): cut the contraction into k-slices as well
+        int ksplit = 1;
+        if (TM == 1) {
+            const long tiles = (long)ceil_div(max_pruned > 0 ? max_pruned : 1, 64) * nct * B;
+            const int stages = d_sim / COS_BK;
+            if (tiles <= COS_SPLIT_BLOCKS / 2) {
+                ksplit = 16;
+                while (ksplit > 1 && (tiles * ksplit > COS_SPLIT_BLOCKS || stages % ksplit || stages / ksplit < COS_NS)) ksplit >>= 1;
+            }
+        }
+        split = ksplit > 1;
         const int BM = TM * 64;
         const int nrt = ceil_div(max_pruned > 0 ? max_pruned : 1, BM);
         // XCD grid XR x XC (8 XCDs): fewest tiles per XCD first, then fewest operand rows per XCD
@@ -629,16 +732,23 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
             const long cost = (long)r * c * 100000 + (long)r * BM + (long)c * COS_BN;
             if (best < 0 || cost < best) { best = cost; XC = xc; R = r; C = c; }
         }
-        const dim3 g((unsigned)(8 * R * C * B));
+        const dim3 g((unsigned)(8 * R * C * B), (unsigned)ksplit);
+        float* dots = (float*)(wsb + w.dots_off);
         const size_t lds = (size_t)COS_NS * (BM + COS_BN) * 128;
         if (TM == 1)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 256, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part, XC, R, C));
+                rnorm, w.NCT, part, XC, R, C, ksplit, dots, nrt, nct));
         else
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 256, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part, XC, R, C));
+                rnorm, w.NCT, part, XC, R, C, 1, dots, nrt, nct));
+        if (split) {
+            const dim3 gr(ceil_div(max_V, 4), B);
+            D3TOM_LAUNCH(COS_REDUCE, st, cos_reduce_argmax<<<gr, 256, 0, st>>>(
+                seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, rnorm, dots, ksplit,
+                nrt * nct * B, nrt, nct, assign, mem));
+        }
     } else {
         const dim3 g(max_V, B);
         if (dt == D3TOM_BF16)
@@ -651,10 +761,12 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
                 rnorm, w.NCT, part));
     }
 
-    const dim3 ga(ceil_div(max_V, 256), B);
-    D3TOM_LAUNCH(MERGE_ASSIGN, st, merge_assign_kernel<<<ga, 256, 0, st>>>(
-        seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
-        assign, mem));
+    if (!split) {                                        // the split-K reduce has written the table already
+        const dim3 ga(ceil_div(max_V, 256), B);
+        D3TOM_LAUNCH(MERGE_ASSIGN, st, merge_assign_kernel<<<ga, 256, 0, st>>>(
+            seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
+            assign, mem));
+    }
 
     const dim3 gs(max_out, B, x1 ? 2 : 1);    // output rows per sample (surplus workgroups of shorter samples exit at once) x payloads
     if (dt == D3TOM_BF16)
