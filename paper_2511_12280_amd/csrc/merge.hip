@@ -494,15 +494,16 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const T* __restrict__ x0, const T* __restrict__ x1, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const int32_t* __restrict__ slot_of_tok,
-    T* __restrict__ y0, T* __restrict__ y1, int32_t* __restrict__ counts_out, int32_t* __restrict__ src_pos_out) {
+    T* __restrict__ y0, T* __restrict__ y1, int32_t* __restrict__ counts_out, int32_t* __restrict__ src_pos_out, int nslice) {
     constexpr int EPC = 16 / sizeof(T);
-    const int o = blockIdx.x, b = blockIdx.y;
+    // a row may be cut into nslice column slices, one workgroup each (few output rows: more workgroups)
+    const int o = blockIdx.x / nslice, slice = blockIdx.x % nslice, b = blockIdx.y;
     // blockIdx.z selects the payload (a second one shares the routing: key and value caches); the
     // index outputs are written by the first payload's workgroups only
     const T* __restrict__ x = blockIdx.z ? x1 : x0;
     T* __restrict__ y = blockIdx.z ? y1 : y0;
-    int32_t* counts = blockIdx.z ? nullptr : counts_out;
-    int32_t* src_pos = blockIdx.z ? nullptr : src_pos_out;
+    int32_t* counts = (blockIdx.z || slice) ? nullptr : counts_out;
+    int32_t* src_pos = (blockIdx.z || slice) ? nullptr : src_pos_out;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int N_m = s.N - s.M;
     if (o >= N_m) return;
@@ -512,6 +513,8 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     T* yrow = y + (size_t)(out_off[b] + o) * d;
     const int nch = d / EPC;
+    const int c_per = (nch + nslice - 1) / nslice;
+    const int c_lo = slice * c_per, c_hi = min(nch, c_lo + c_per);          // this workgroup's 16-byte chunks
     int src = -1, len = 1, r = 0;
     // token -> slot table of this sample, read four entries per lane; a wave takes a contiguous part
     // of it (a multiple of 256 entries so that every lane takes part in each ballot)
@@ -574,7 +577,7 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
         if (tid == 0 && src_pos && (o < s.vs || o >= s.vs + s.k)) src_pos[out_off[b] + o] = src;
         const uint4* in = reinterpret_cast<const uint4*>(x + (size_t)(s.tok0 + src) * d);
         uint4* out = reinterpret_cast<uint4*>(yrow);
-        for (int c = tid; c < nch; c += 256) out[c] = in[c];
+        for (int c = c_lo + tid; c < c_hi; c += 256) out[c] = in[c];
         return;
     }
     // members with ordinal in [win0, win0 + SCAT_LIST) -> list (only when the first scan did not fit)
@@ -597,7 +600,7 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
             }
         }
     };
-    for (int cb = 0; cb < nch; cb += 256 * CPT) {         // uniform trip count: the loop body has barriers
+    for (int cb = c_lo; cb < c_hi; cb += 256 * CPT) {     // uniform trip count: the loop body has barriers
         const int c0 = cb + tid;
         float acc[CPT][EPC];
 #pragma unroll
@@ -612,13 +615,25 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
                 __syncthreads();
             }
             int t = 0;
+            if constexpr (CPT == 1)                        // half-row workgroups: registers to spare for 8 rows in flight
+            for (; t + 8 <= ln; t += 8) {
+                uint4 w[8][CPT];
+#pragma unroll
+                for (int m = 0; m < 8; ++m) {
+                    const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)list[t + m] * d);
+#pragma unroll
+                    for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[m][u] = (c < c_hi) ? row[c] : make_uint4(0, 0, 0, 0); }
+                }
+#pragma unroll
+                for (int m = 0; m < 8; ++m) add_row(acc, w[m]);
+            }
             for (; t + 4 <= ln; t += 4) {
                 uint4 w[4][CPT];
 #pragma unroll
                 for (int m = 0; m < 4; ++m) {
                     const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)list[t + m] * d);
 #pragma unroll
-                    for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[m][u] = (c < nch) ? row[c] : make_uint4(0, 0, 0, 0); }
+                    for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[m][u] = (c < c_hi) ? row[c] : make_uint4(0, 0, 0, 0); }
                 }
 #pragma unroll
                 for (int m = 0; m < 4; ++m) add_row(acc, w[m]);
@@ -627,14 +642,14 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
                 uint4 w[CPT];
                 const uint4* row = reinterpret_cast<const uint4*>(xv + (size_t)list[t] * d);
 #pragma unroll
-                for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[u] = (c < nch) ? row[c] : make_uint4(0, 0, 0, 0); }
+                for (int u = 0; u < CPT; ++u) { const int c = c0 + 256 * u; w[u] = (c < c_hi) ? row[c] : make_uint4(0, 0, 0, 0); }
                 add_row(acc, w);
             }
         }
 #pragma unroll
         for (int u = 0; u < CPT; ++u) {
             const int c = c0 + 256 * u;
-            if (c < nch) {
+            if (c < c_hi) {
                 uint4 w;
                 if constexpr (sizeof(T) == 2) {
                     w.x = pack_bf16x2(acc[u][0] / inv, acc[u][1] / inv);
@@ -768,15 +783,17 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
             assign, mem));
     }
 
-    const dim3 gs(max_out, B, x1 ? 2 : 1);    // output rows per sample (surplus workgroups of shorter samples exit at once) x payloads
-    if (dt == D3TOM_BF16)
-        D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<uint16_t, 2><<<gs, 256, 0, st>>>(
-            (const uint16_t*)x0, (const uint16_t*)x1, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode,
-            out_off, mem, (uint16_t*)y0, (uint16_t*)y1, counts, src_pos));
-    else
-        D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<float, 2><<<gs, 256, 0, st>>>(
-            (const float*)x0, (const float*)x1, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode,
-            out_off, mem, (float*)y0, (float*)y1, counts, src_pos));
+    // few output rows (short sequences): two workgroups per row, half a row each, so that more CUs stream
+    const int nch = d / epc;
+    const int nslice = ((long)max_out * B * (x1 ? 2 : 1) < 768 && nch >= 512) ? 2 : 1;
+    const dim3 gs(max_out * nslice, B, x1 ? 2 : 1);    // output rows (x slices) per sample x payloads; surplus workgroups exit at once
+#define D3TOM_SCATTER(TYPE, CPT)                                                                                        \
+    D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<TYPE, CPT><<<gs, 256, 0, st>>>(                                \
+        (const TYPE*)x0, (const TYPE*)x1, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode,   \
+        out_off, mem, (TYPE*)y0, (TYPE*)y1, counts, src_pos, nslice))
+    if (dt == D3TOM_BF16) { if (nslice == 2) D3TOM_SCATTER(uint16_t, 1); else D3TOM_SCATTER(uint16_t, 2); }
+    else                  { if (nslice == 2) D3TOM_SCATTER(float, 1); else D3TOM_SCATTER(float, 2); }
+#undef D3TOM_SCATTER
     return D3TOM_OK;
 }
 
