@@ -247,12 +247,12 @@ __global__ __launch_bounds__(256) void imp_finish_kernel(
     const int V = min(min(vis_count[b], max_V), N - vs);
     if (j >= V) return;
     float s = 0.f;
-    for (int h0 = 0; h0 < H; h0 += 8) {                    // 8 independent loads in flight, added in head order
-        float a[8];
+    for (int h0 = 0; h0 < H; h0 += 32) {                   // 32 independent loads in flight, added in head order
+        float a[32];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) a[u] = (h0 + u < H) ? sp[(size_t)(b * H + h0 + u) * VPAD + j] : 0.f;
+        for (int u = 0; u < 32; ++u) a[u] = (h0 + u < H) ? sp[(size_t)(b * H + h0 + u) * VPAD + j] : 0.f;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += a[u];
+        for (int u = 0; u < 32; ++u) s += a[u];
     }
     scores[score_off[b] + j] = s / (float)H;
 }

@@ -86,15 +86,25 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
     const T* row = f + (size_t)(s.tok0 + s.vs + j) * d;
     constexpr int EPC = 16 / sizeof(T);       // elements per 16-byte chunk
     float ss = 0.f;
-    for (int c = lane; c < d / EPC; c += 64) {
-        const uint4 w = *reinterpret_cast<const uint4*>(row + (size_t)c * EPC);
-        if constexpr (sizeof(T) == 2) {
-            const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+    const int nch = d / EPC;
+    for (int c0 = 0; c0 < nch; c0 += 64 * 8) {             // 8 independent 16-byte loads per lane in flight
+        uint4 w8[8];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) { const float a = bf16_lo(ww[e]), c2 = bf16_hi(ww[e]); ss += a * a; ss += c2 * c2; }
-        } else {
-            const float a0 = __uint_as_float(w.x), a1 = __uint_as_float(w.y), a2 = __uint_as_float(w.z), a3 = __uint_as_float(w.w);
-            ss += a0 * a0; ss += a1 * a1; ss += a2 * a2; ss += a3 * a3;
+        for (int u = 0; u < 8; ++u) {
+            const int c = c0 + u * 64 + lane;
+            w8[u] = (c < nch) ? *reinterpret_cast<const uint4*>(row + (size_t)c * EPC) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint4 w = w8[u];
+            if constexpr (sizeof(T) == 2) {
+                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { const float a = bf16_lo(ww[e]), c2 = bf16_hi(ww[e]); ss += a * a; ss += c2 * c2; }
+            } else {
+                const float a0 = __uint_as_float(w.x), a1 = __uint_as_float(w.y), a2 = __uint_as_float(w.z), a3 = __uint_as_float(w.w);
+                ss += a0 * a0; ss += a1 * a1; ss += a2 * a2; ss += a3 * a3;
+            }
         }
     }
     ss = wave_sum(ss);
@@ -463,12 +473,12 @@ __global__ __launch_bounds__(256) void merge_assign_kernel(
         const int nct = tiled ? (s.k + COS_BN - 1) / COS_BN : 1;
         const float2* pb = part + (size_t)b * NCT * max_V;
         float bv = -INFINITY; int bi = 0;
-        for (int c0 = 0; c0 < nct; c0 += 8) {              // 8 independent loads in flight
-            float2 a[8];
+        for (int c0 = 0; c0 < nct; c0 += 16) {             // 16 independent loads in flight
+            float2 a[16];
 #pragma unroll
-            for (int w = 0; w < 8; ++w) a[w] = (c0 + w < nct) ? pb[(size_t)(c0 + w) * max_V + i] : make_float2(-INFINITY, 0.f);
+            for (int w = 0; w < 16; ++w) a[w] = (c0 + w < nct) ? pb[(size_t)(c0 + w) * max_V + i] : make_float2(-INFINITY, 0.f);
 #pragma unroll
-            for (int w = 0; w < 8; ++w) if (a[w].x > bv) { bv = a[w].x; bi = __float_as_int(a[w].y); }
+            for (int w = 0; w < 16; ++w) if (a[w].x > bv) { bv = a[w].x; bi = __float_as_int(a[w].y); }
         }
         slot = min(max(bi, 0), s.k - 1);
         tok = min(max(pruned[(size_t)b * max_V + i], 0), s.V - 1);
