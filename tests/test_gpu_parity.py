@@ -178,6 +178,38 @@ def test_serving_shape_ragged_subset():
         check_full_sample(step, b, S, kept, slot, mout, assign_rows=rng.choice(pruned, size=96, replace=False))
 
 
+def test_serving_shape_full_batch_of_16():
+    """The whole ragged serving batch in one launch set (the configuration the kernels' batch mapping and
+    the XCD-aware grids see in production): every sample's index outputs are checked for consistency, four
+    samples (first, last, fewest kept, most deciders) are checked against the oracle stage by stage, and
+    the attention over the 16 merged lengths is checked on sampled query rows."""
+    wl = W.WORKLOADS["serving_b16"]
+    proj = W.Projections(wl)
+    draws = W.serving_draws(wl)
+    gens = [W.SampleGen(wl, proj, seed=dr["seed"]) for dr in draws]
+    samples = [g.step(dr["D"]) for g, dr in zip(gens, draws)]
+    keeps = [oracle.keep_count(wl.V, dr["keep_ratio"]) for dr in draws]
+    rng = np.random.default_rng(5)
+    step = GpuStep(samples, keeps, "bf16")
+    S = step.importance(); kept, slot = step.select_topk(); mout = step.merge()
+    for b in range(wl.B):
+        assert len(kept[b]) == keeps[b] and (np.diff(kept[b]) > 0).all()
+        np.testing.assert_array_equal(np.where(slot[b] >= 0)[0], kept[b])
+        assert mout["counts"][b].sum() == wl.V and mout["counts"][b].min() >= 1
+        np.testing.assert_array_equal(mout["assign"][b][kept[b]], np.arange(keeps[b]))
+        np.testing.assert_array_equal(np.bincount(mout["assign"][b], minlength=keeps[b]), mout["counts"][b])
+        assert mout["y"][b].shape == (wl.N - (wl.V - keeps[b]), wl.d)
+    detail = sorted({0, wl.B - 1, int(np.argmin(keeps)), int(np.argmax([dr["D"] for dr in draws]))})
+    for b in detail:
+        pruned = np.setdiff1d(np.arange(wl.V), kept[b])
+        check_full_sample(step, b, S, kept, slot, mout, assign_rows=rng.choice(pruned, size=64, replace=False))
+    qkv = [g.attention_inputs(wl.N - (wl.V - k), dr["D"]) for g, dr, k in zip(gens, draws, keeps)]
+    outs = gpu_attend(qkv, "bf16")
+    for b in detail[:3]:
+        rows = rng.choice(qkv[b][0].shape[0], size=24, replace=False)
+        check_attend(outs[b], *qkv[b], "bf16", rows=rows)
+
+
 # ---- edge cases, determinism, error paths ---------------------------------------------------------------
 def test_edge_counts():
     # k = 1 (everything merges into one token), D = 1, visual block at the very end
