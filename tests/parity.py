@@ -61,10 +61,12 @@ class GpuStep:
         torch.cuda.synchronize()
         return self.split(B.to_host(self.kept_idx), self.lay.keep), self.split(B.to_host(self.slot_of), self.lay.V)
 
-    def merge(self, kept: Optional[List[np.ndarray]] = None):
+    def merge(self, kept: Optional[List[np.ndarray]] = None, sim_rows: Optional[np.ndarray] = None):
+        """`sim_rows` [sum N, d_sim]: separate features for the cosine (the payload stays `x`)."""
         if kept is not None:
             self.kept_idx.copy_(torch.from_numpy(np.concatenate(kept).astype(np.int32)))
-        B.d3tom_merge(self.x, None, self.lay, self.kept_idx, self.mode, self.y, self.assign, self.counts, self.src_pos,
+        sim = B.to_device(sim_rows, self.dtype) if sim_rows is not None else None
+        B.d3tom_merge(self.x, sim, self.lay, self.kept_idx, self.mode, self.y, self.assign, self.counts, self.src_pos,
                       self.ws_merge)
         torch.cuda.synchronize()
         lay = self.lay

@@ -231,6 +231,24 @@ def test_edge_counts():
     np.testing.assert_array_equal(mout["counts"][0], [1196, 1, 1, 1, 1])
 
 
+# ---- cosine taken on separate features (Section 4.4 compares keys while other rows are merged) --------
+@pytest.mark.parametrize("dtype,d_sim", [("bf16", 256), ("bf16", 4 * 128 + 8), ("f32", 96)])
+def test_merge_with_separate_similarity_features(dtype, d_sim):
+    # d_sim = 256: MFMA path (split along the contraction, short sequence); 520: not a multiple of 64 -> generic path
+    shapes = [(12, 500, 20, 0.3), (0, 260, 5, 0.6)]
+    samples, keeps, sims = [], [], []
+    for i, (P, V, O, keep) in enumerate(shapes):
+        c = W.random_case(800 + i, P + V + O, 4 * 128, 4, P, V, 4, dtype=dtype, centres=max(4, V // 7))
+        f = W.random_case(900 + i, P + V + O, d_sim, 1, P, V, 4, dtype=dtype, centres=max(4, V // 9))["x"]
+        samples.append(c); keeps.append(oracle.keep_count(V, keep)); sims.append(f)
+    rng = np.random.default_rng(9)
+    kept = [np.sort(rng.choice(s["V"], size=k, replace=False)).astype(np.int32) for s, k in zip(samples, keeps)]
+    out = GpuStep(samples, keeps, dtype).merge(kept, sim_rows=np.concatenate(sims))
+    for b, s in enumerate(samples):
+        check_assign(out["assign"][b], sims[b], s["vis_start"], s["V"], kept[b])          # routing follows `sim`
+        check_merge({key: out[key][b] for key in out}, s["x"], s["vis_start"], s["V"], kept[b], dtype)   # payload is `x`
+
+
 # ---- KV-cache variant (Section 4.4): one routing from the key cache, both caches aggregated ------------
 @pytest.mark.parametrize("mode", ["mean", "sum"])
 def test_merge_kv_ragged_batch(mode):
