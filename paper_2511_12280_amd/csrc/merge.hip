@@ -210,15 +210,19 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     // split-K: slice blockIdx.y of the contraction (ksplit slices of nkt stages each)
     const int nkt = (d / COS_BK) / ksplit;
     const int kt0 = (int)blockIdx.y * nkt;
+    // LDS destinations are wave-uniform: this wave's first row of the A (B) tile, made a scalar once so
+    // that a load costs one scalar add for its M0 value and no vector instruction
+    const uint32_t ring0 = (uint32_t)(size_t)(lds_ptr_t)ring;
+    const uint32_t a_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (BM / 4) * 128);
+    const uint32_t b_lds = __builtin_amdgcn_readfirstlane(ring0 + BM * 128 + wave * (COS_BN / 4) * 128);
     auto issue = [&](int kt, int stage) {
-        char* sb = ring + stage * STAGE;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(sb + (wave * (BM / 4) + i * 8) * 128), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(size_t)(a_lds + stage * STAGE + i * 8 * 128), 16,
                                                      a_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(sb + BM * 128 + (wave * (COS_BN / 4) + i * 8) * 128), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(size_t)(b_lds + stage * STAGE + i * 8 * 128), 16,
                                                      b_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
     };
 
