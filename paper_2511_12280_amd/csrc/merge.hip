@@ -215,16 +215,20 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const uint32_t ring0 = (uint32_t)(size_t)(lds_ptr_t)ring;
     const uint32_t a_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (BM / 4) * 128);
     const uint32_t b_lds = __builtin_amdgcn_readfirstlane(ring0 + BM * 128 + wave * (COS_BN / 4) * 128);
-    auto issue = [&](int kt, int stage) {
+    // loads [n0, n1) of a stage's LPS loads (A tile first, then B tile)
+    auto issue_part = [&](int kt, int stage, int n0, int n1) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(size_t)(a_lds + stage * STAGE + i * 8 * 128), 16,
-                                                     a_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
+            if (i >= n0 && i < n1)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(size_t)(a_lds + stage * STAGE + i * 8 * 128), 16,
+                                                         a_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(size_t)(b_lds + stage * STAGE + i * 8 * 128), 16,
-                                                     b_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
+            if (A_LD + i >= n0 && A_LD + i < n1)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (lds_ptr_t)(size_t)(b_lds + stage * STAGE + i * 8 * 128), 16,
+                                                         b_off[i], (kt0 + kt) * (COS_BK * 2), 0, 0);
     };
+    auto issue = [&](int kt, int stage) { issue_part(kt, stage, 0, LPS); };
 
     f32x16 acc[TM][2];
 #pragma unroll
@@ -242,8 +246,10 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
 
     // one stage: (optionally) start the loads of the stage COS_NS-1 ahead, then feed stage kt to the MFMAs
+    // The loads of the stage COS_NS-1 ahead are spread over the four k-steps, each piece right behind that
+    // step's MFMAs, so that their scalar set-up issues while the matrix pipe is busy.
+    constexpr int LPK = (LPS + 3) / 4;
     auto stage = [&](int kt, const bool prefetch) {
-        if (prefetch) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
         const char* sb = ring + (kt % COS_NS) * STAGE;
         // operand fragments are read one k-step ahead of the MFMAs that use them, so the LDS latency
         // of step kk + 1 is covered by the matrix work of step kk
@@ -266,6 +272,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+            if (prefetch) issue_part(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS, kk * LPK, min((kk + 1) * LPK, LPS));
             __builtin_amdgcn_sched_barrier(0);
         }
     };
