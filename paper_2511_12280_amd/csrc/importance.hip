@@ -6,7 +6,7 @@
 // decider rows are ever evaluated, in two sweeps over K:
 //
 //   sweep 1 (stats)   per (head, decider): running max and sum of exp2 over all keys, computed per
-//                     256-key chunk by one workgroup each and combined later in a fixed order
+//                     512-key chunk by one workgroup each and combined later in a fixed order
 //   sweep 2 (scores)  per (head, visual key): sum over deciders of exp2(logit - logsumexp), one row
 //                     per head; a small third kernel adds the H rows in head order (no atomics)
 //
@@ -14,7 +14,8 @@
 // operands read straight from HBM/L2 in the MFMA operand layout (each lane reads dh/4 contiguous
 // elements of its row; the contraction index is permuted identically for both operands, which a
 // dot product does not see).  Everything is bandwidth bound: K is streamed twice, the second time
-// usually from the memory-side cache.
+// usually from the memory-side cache; with many deciders (64 and up) the exp2 / max arithmetic per logit
+// becomes a comparable share of the run time.
 //
 // The generic path (any float type / head size) is a plain one-thread-per-output kernel pair.
 #include "common.hpp"
@@ -63,7 +64,7 @@ __device__ __forceinline__ void load_frag(const uint16_t* row, int g, bool valid
 
 constexpr int IMP_NB = 4;       // 16-decider blocks whose query fragments are fetched together
 
-// (running max, running sum of exp2) of decider rows over one 128-key chunk of one head
+// (running max, running sum of exp2) of decider rows over one IMP_KC_STATS-key chunk of one head
 template <int DH>
 __global__ __launch_bounds__(256) void imp_stats_bf16(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
