@@ -206,6 +206,8 @@ int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
  * batch, no mask, no dropout).  bf16: MFMA with float32 online-softmax state; f32: plain float.
  *
  *   q, k, v     [cu_seqlens[B], H, dh] dt
+ *   scale       logit scale, finite and > 0 (1/sqrt(dh) in the paper's models); otherwise
+ *               D3TOM_ERR_INVALID_ARG (same rule in d3tom_importance)
  *   cu_seqlens  int32[B+1]  first token of each sample
  *   max_seqlen  host-known longest sample
  *   o           [cu_seqlens[B], H, dh] dt  out

@@ -354,6 +354,7 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
     (void)ws; (void)ws_bytes;
     if (!q || !k || !v || !o || !cu_seqlens) return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || max_seqlen < 1 || H < 1 || dh < 1) return D3TOM_ERR_INVALID_ARG;
+    if (!(scale > 0.f) || !(scale < 3.0e38f)) return D3TOM_ERR_INVALID_ARG;      // the running max is taken on raw logits
     if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return D3TOM_ERR_INVALID_ARG;
     if (dh > 256 || (dt == D3TOM_BF16 ? (dh % 8) : (dh % 4))) return D3TOM_ERR_UNSUPPORTED;

@@ -341,6 +341,7 @@ extern "C" int d3tom_importance(const void* q, const void* k, int dt,
     if (B < 1 || H < 1 || dh < 1 || max_N < 1 || max_V < 1 || max_V > max_N || min_D < 0 || max_D < min_D)
         return D3TOM_ERR_INVALID_ARG;
     if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
+    if (!(scale > 0.f) || !(scale < 3.0e38f)) return D3TOM_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k)) return D3TOM_ERR_INVALID_ARG;
     if (min_D == 0) return D3TOM_ERR_NO_DECIDERS;
     if (max_D > D3TOM_MAX_DECIDERS) return D3TOM_ERR_UNSUPPORTED;

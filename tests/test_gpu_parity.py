@@ -348,4 +348,12 @@ def test_error_statuses():
     with pytest.raises(B.D3tomError) as e:
         B.d3tom_attend(q, q, q, cu, 8, 1.0, torch.zeros_like(q))
     assert e.value.status == B.D3TOM_ERR_UNSUPPORTED
+    q2 = torch.zeros((8, 1, 64), dtype=torch.bfloat16, device="cuda")
+    for bad_scale in (0.0, -0.125, float("inf"), float("nan")):                # the logit scale must be finite and > 0
+        with pytest.raises(B.D3tomError) as e:
+            B.d3tom_attend(q2, q2, q2, cu, 8, bad_scale, torch.zeros_like(q2))
+        assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+        with pytest.raises(B.D3tomError) as e:
+            B.d3tom_importance(step.q, step.k, step.lay, bad_scale, step.scores, step.ws_imp)
+        assert e.value.status == B.D3TOM_ERR_INVALID_ARG
     torch.cuda.synchronize()
