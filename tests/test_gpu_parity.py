@@ -61,6 +61,23 @@ def test_f32_generic_case_and_odd_head_size():
     _chain([c], [oracle.keep_count(80, 0.25)], "bf16")
 
 
+# ---- tile-edge shapes: counts that sit exactly on, one below and one above the kernels' tile sizes --------
+@pytest.mark.parametrize("P,V,O,D,k", [
+    (0, 512, 16, 16, 128),       # keys = one 512-key chunk + deciders, kept = one 128-slot column tile, pruned = 6 x 64
+    (1, 513, 33, 33, 129),       # one past every boundary
+    (0, 511, 256, 256, 127),     # the largest decider set, one below the boundaries
+    (3, 257, 17, 17, 256),       # a single pruned token
+    (5, 640, 48, 47, 64),        # 9 row tiles x 1 half-filled column tile (split along the contraction)
+])
+def test_tile_edge_shapes(P, V, O, D, k):
+    c = W.random_case(1000 + V + k, P + V + O, 2 * 128, 2, P, V, D, dtype="bf16", centres=max(4, V // 9))
+    step, S, kept, mout, stats = _chain([c], [k], "bf16")
+    assert mout["y"][0].shape[0] == P + k + O
+    n_m = P + k + O
+    qkv = W.random_qkv(2000 + n_m, n_m, 2, 128, "bf16")
+    check_attend(gpu_attend([qkv], "bf16")[0], *qkv, "bf16")
+
+
 # ---- ragged batch ----------------------------------------------------------------------------------
 def test_ragged_batch_bf16():
     shapes = [(20, 300, 30, 9, 0.2), (64, 513, 64, 33, 0.5), (1, 128, 5, 1, 0.1), (7, 129, 300, 100, 0.33), (0, 64, 2, 2, 1.0)]
