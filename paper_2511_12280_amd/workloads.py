@@ -264,3 +264,35 @@ def mask_trajectory(seed: int, n_prefix: int, n_response: int, steps: int, mask_
         states.append(state.copy())
     return states
 
+
+
+def stack_case(seed: int, L: int, d: int, H: int, F: int, P: int, V: int, O: int, D: int, std: float = 0.02,
+               gain_jitter: float = 0.0, centres: int = 16, noise: float = 0.3) -> dict:
+    """Inputs of one denoising step through a stack of L blocks, all rounded to bf16: random-init weights
+    ~ N(0, std) stored as [out, in] rows, RMSNorm gains 1 (+ N(0, gain_jitter) so that a test can see them),
+    hidden states of prompt | clustered visual tokens | response, of which D response positions hold decoded
+    tokens (the deciders, ascending) and the others all share the one [MASK] embedding."""
+    rng = np.random.default_rng([seed, 11])
+    N = P + V + O
+
+    def w(rows, cols):
+        return round_to((std * rng.standard_normal((rows, cols))).astype(np.float32), "bf16")
+
+    def g():
+        return round_to((1.0 + gain_jitter * rng.standard_normal(d)).astype(np.float32), "bf16")
+
+    blocks = [dict(attn_norm=g(), wq=w(d, d), wk=w(d, d), wv=w(d, d), wo=w(d, d), ffn_norm=g(),
+                   w_gate=w(F, d), w_up=w(F, d), w_down=w(d, F)) for _ in range(L)]
+    x = rng.standard_normal((N, d)).astype(np.float32)
+    if V > 0:
+        cen = rng.standard_normal((max(1, centres), d)).astype(np.float32)
+        pick = rng.integers(0, max(1, centres), size=V)
+        x[P:P + V] = cen[pick] + np.float32(noise) * rng.standard_normal((V, d)).astype(np.float32)
+    D = min(D, O)
+    dec_idx = np.sort(P + V + rng.permutation(O)[:D]).astype(np.int32)
+    mask_vec = rng.standard_normal(d).astype(np.float32)
+    is_mask = np.ones(N, dtype=bool)
+    is_mask[:P + V] = False
+    is_mask[dec_idx] = False
+    x[is_mask] = mask_vec
+    return dict(x=round_to(x, "bf16"), blocks=blocks, dec_idx=dec_idx, vis_start=P, V=V, N=N, D=D, H=H, d=d, F=F, L=L)
