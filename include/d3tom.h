@@ -239,6 +239,93 @@ int d3tom_update_deciders(const int32_t* prev_ids, const int32_t* cur_ids, int m
                           int32_t* dec_idx, int32_t* dec_off, int32_t* dec_count, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * The blocks around the merge layer (Algorithm 1, the loop over layers l = 1 .. L_model: every layer
+ * is a self-attention part followed by a feed-forward part, the merge sits between the two inside
+ * layer l*; Section 4.3 counts a layer as 4 n d^2 + 2 n^2 d + 3 n d m FLOPs).  The paper's models are
+ * Llama-style: pre-norm residual blocks with RMSNorm, rotary position embedding on q and k, and a
+ * SwiGLU feed-forward part.  bf16 storage, float32 arithmetic, one rounding where a tensor is stored.
+ * ---------------------------------------------------------------------------------------- */
+
+/* d3tom_rmsnorm: y[r, :] = x[r, :] / sqrt(mean(x[r, :]^2) + eps) * gain.
+ *   x, y  [rows, d] bf16 (y may be x)   gain [d] bf16   d a multiple of 8, at most 8192; eps >= 0 */
+int d3tom_rmsnorm(const void* x, const void* gain, int rows, int d, float eps, void* y, void* stream);
+
+/* d3tom_rope: rotary position embedding, in place on q and k [rows, H, dh] bf16.  Channel c < dh/2 of
+ * every head is paired with channel c + dh/2; the pair is rotated by pos[r] * theta^(-2c/dh) radians.
+ * After the merge the kept tokens keep their original positions (Section 3.2 removes positions, it
+ * does not renumber them): pos is then the src_pos output of d3tom_merge.
+ *   pos  int32[rows]   dh a multiple of 16, at most 256   theta > 1 */
+int d3tom_rope(void* q, void* k, const int32_t* pos, int rows, int H, int dh, float theta, void* stream);
+
+/* d3tom_linear: out = a w^T, the projections of a block (the 4 n d^2 and 3 n d m terms), on MFMA.
+ *   a         [rows, K] bf16
+ *   w         [n_w_rows, K] bf16: one row per output feature
+ *   epilogue  D3TOM_LINEAR_PLAIN     out[rows, n_w_rows] = a w^T.  With 0 < out_chunk < n_w_rows the
+ *                                    result is written as n_w_rows / out_chunk matrices [rows, out_chunk]
+ *                                    one after the other (q, k, v from one stacked weight).
+ *             D3TOM_LINEAR_RESIDUAL  out = residual + a w^T, residual [rows, n_w_rows] bf16; out may be
+ *                                    the residual buffer itself.
+ *             D3TOM_LINEAR_SWIGLU    w = F gate rows followed by F up rows (n_w_rows = 2F);
+ *                                    out[rows, F] = silu(a w_gate^T) * (a w_up^T).
+ *   out_chunk 0 = one matrix; otherwise a multiple of 8 dividing n_w_rows (PLAIN only)
+ * K must be a multiple of 64 and the output row length a multiple of 8; each operand below 2 GiB;
+ * otherwise D3TOM_ERR_UNSUPPORTED. */
+typedef enum { D3TOM_LINEAR_PLAIN = 0, D3TOM_LINEAR_RESIDUAL = 1, D3TOM_LINEAR_SWIGLU = 2 } d3tom_linear_epilogue;
+int d3tom_linear(const void* a, const void* w, int rows, int n_w_rows, int K, int epilogue,
+                 const void* residual, void* out, int out_chunk, void* stream);
+/* The same with the workgroup's row-tile height fixed to tile * 64 rows (tile = 1, 2 or 4) instead of
+ * chosen from the problem size; for tuning and tests. */
+int d3tom_linear_tile(const void* a, const void* w, int rows, int n_w_rows, int K, int epilogue,
+                      const void* residual, void* out, int out_chunk, int tile, void* stream);
+
+/* Weights of one block, device pointers, bf16. */
+typedef struct {
+    const void* attn_norm;   /* [d]      RMSNorm gain in front of the attention part        */
+    const void* w_qkv;       /* [3d, d]  rows of W_Q, then W_K, then W_V                      */
+    const void* w_o;         /* [d, d]   attention output projection                          */
+    const void* ffn_norm;    /* [d]      RMSNorm gain in front of the feed-forward part       */
+    const void* w_gate_up;   /* [2F, d]  F gate rows, then F up rows                          */
+    const void* w_down;      /* [d, F]                                                        */
+} d3tom_block_weights;
+
+/* Workspace of d3tom_stack_step for a sequence of N tokens (V of them visual, at most max_D
+ * deciders), hidden size d = H * dh, feed-forward width F. */
+size_t d3tom_stack_workspace_bytes(int N, int d, int H, int F, int V, int max_D);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_stack_step — one denoising step through all L blocks for one sample (Algorithm 1, the body
+ * of the loop over t without Embed / Decode):
+ *
+ *   for l = 1 .. L:   a = rmsnorm(h);  q, k, v = a W_Q^T, a W_K^T, a W_V^T;  rope(q, k) at the tokens'
+ *                     original positions;  h~ = h + attend(q, k, v) W_O^T
+ *                     if l == merge_layer and D > 0:  S = importance(q, k, deciders);  kept = top-k(S);
+ *                         h~ = merge(h~, kept)          -- N -> N - (V - keep_k) rows from here on
+ *                     h = h~ + (silu(f W_gate^T) * (f W_up^T)) W_down^T  with  f = rmsnorm(h~)
+ *
+ * i.e. the importance map comes from the attention the merge block itself just computed, the cosine is
+ * taken on that block's post-attention hidden states, and the block's own feed-forward part already runs
+ * on the shortened sequence.  D == 0 (first step, empty decider set) or merge_layer outside 1 .. L runs
+ * every block at full length.  Logit scale 1/sqrt(dh); no final norm, no decoding head.
+ *
+ *   x          [N, d] bf16     hidden states entering block 1 (never written)
+ *   blocks     HOST array of L d3tom_block_weights (device pointers inside)
+ *   dec_idx    int32[D]  decider positions (device; may be NULL when D == 0)
+ *   vis_start, V, keep_k   the visual block and the kept count (d3tom_keep_count)
+ *   mode       d3tom_merge_mode
+ *   y          [n_out, d] bf16 out, n_out = N - (V - keep_k) when merging, else N (room for N rows is
+ *              always enough)
+ *   src_pos    int32[n_out] out or NULL: original position of every output row
+ *   scores_out float[V], kept_idx_out int32[keep_k], assign_out int32[V]: the merge layer's intermediate
+ *              results, out or NULL (written only when merging)
+ *   n_out      HOST int out or NULL
+ * dh must be 64 or 128, d and F multiples of 64.
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L, const d3tom_block_weights* blocks /* host */,
+                     int merge_layer, const int32_t* dec_idx, int D, int vis_start, int V, int keep_k, int mode,
+                     float eps, float theta, void* y, int32_t* src_pos, float* scores_out, int32_t* kept_idx_out,
+                     int32_t* assign_out, int* n_out /* host */, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (diagnostics; used by the benchmark for its roofline figures).  While enabled,
  * every kernel launch of the four entry points is bracketed by HIP events on the caller's stream.
  * d3tom_profile_collect waits for the recorded events, adds up milliseconds and launch counts per

@@ -40,11 +40,14 @@ def round_bf16(a) -> np.ndarray:
     return np.ldexp(np.rint(m * 256.0), e - 8)   # rint: ties to even
 
 
-def _store_fn(store) -> Callable[[np.ndarray], np.ndarray]:
+def _store_fn(store, jitter: float = 0.0, seed: int = 0) -> Callable[[np.ndarray], np.ndarray]:
     if store is None:
         return lambda a: np.asarray(a, dtype=np.float64)
     if store == "bf16":
-        return round_bf16
+        if jitter == 0.0:
+            return round_bf16
+        rng = np.random.default_rng(seed)
+        return lambda a: round_bf16(np.asarray(a, dtype=np.float64) * (1.0 + jitter * rng.standard_normal(np.shape(a))))
     raise ValueError("store must be None or 'bf16'")
 
 
@@ -103,7 +106,8 @@ class Block:
 
 def stack_step(x, blocks: Sequence[Block], H: int, dec_idx, vis_start: int, V: int, keep_k: int,
                merge_layer: int, eps: float = 1e-5, theta: float = 10000.0, store="bf16",
-               kept_override=None, assign_override=None, mode: str = "mean") -> dict:
+               kept_override=None, assign_override=None, mode: str = "mean", jitter: float = 0.0,
+               jitter_seed: int = 0) -> dict:
     """One denoising step: hidden states x [N, d] through all blocks.
 
     Per block l = 1 .. L (pre-norm residual blocks):
@@ -119,8 +123,12 @@ def stack_step(x, blocks: Sequence[Block], H: int, dec_idx, vis_start: int, V: i
     kept_override / assign_override: kept list / assignment to use instead of the oracle's own top-k /
     argmax (for chained parity checks, so that an excused near-tie does not cascade); the oracle's own
     choices are still returned next to them.
+    jitter: relative Gaussian perturbation applied to every value just before it is rounded for storage
+    (0 = none).  Not part of the method: a test uses it to measure how far the stored result moves when the
+    exact values move by a few float32 ulps, which is the difference any float32 implementation has to the
+    float64 one, and sizes its whole-step tolerance from that.
     Returns y [N_out, d], src_pos [N_out] and the merge layer's intermediate results."""
-    rt = _store_fn(store)
+    rt = _store_fn(store, jitter, jitter_seed)
     h = np.asarray(x, dtype=np.float64)
     N, d = h.shape
     dh = d // H

@@ -28,9 +28,11 @@ D3TOM_F32, D3TOM_BF16 = 0, 1
 D3TOM_MERGE_MEAN, D3TOM_MERGE_SUM = 0, 1
 D3TOM_OP_IMPORTANCE, D3TOM_OP_SELECT_TOPK, D3TOM_OP_MERGE, D3TOM_OP_ATTEND = range(4)
 D3TOM_MAX_VISUAL, D3TOM_MAX_DECIDERS = 16384, 256
+D3TOM_LINEAR_PLAIN, D3TOM_LINEAR_RESIDUAL, D3TOM_LINEAR_SWIGLU = range(3)
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
            "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_update_deciders",
+           "d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_linear_tile", "d3tom_stack_workspace_bytes", "d3tom_stack_step",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
 _vp, _i, _f, _d, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_double, ctypes.c_size_t
@@ -59,7 +61,26 @@ _lib.d3tom_update_deciders.restype = _i
 _lib.d3tom_update_deciders.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
+_lib.d3tom_rmsnorm.restype = _i
+_lib.d3tom_rmsnorm.argtypes = [_vp, _vp, _i, _i, _f, _vp, _vp]
+_lib.d3tom_rope.restype = _i
+_lib.d3tom_rope.argtypes = [_vp, _vp, _vp, _i, _i, _i, _f, _vp]
+_lib.d3tom_linear.restype = _i
+_lib.d3tom_linear.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _i, _vp]
+_lib.d3tom_linear_tile.restype = _i
+_lib.d3tom_linear_tile.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _i, _i, _vp]
 
+
+class BlockWeights(ctypes.Structure):
+    """d3tom_block_weights: device pointers of one block's parameters."""
+    _fields_ = [(n, _vp) for n in ("attn_norm", "w_qkv", "w_o", "ffn_norm", "w_gate_up", "w_down")]
+
+
+_lib.d3tom_stack_workspace_bytes.restype = _sz
+_lib.d3tom_stack_workspace_bytes.argtypes = [_i] * 6
+_lib.d3tom_stack_step.restype = _i
+_lib.d3tom_stack_step.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.POINTER(BlockWeights), _i, _vp, _i, _i, _i, _i, _i,
+                                  _f, _f, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i), _vp, _sz, _vp]
 
 _lib.d3tom_profile_enable.restype = _i
 _lib.d3tom_profile_enable.argtypes = [_i]
@@ -262,6 +283,73 @@ def d3tom_update_deciders(prev_ids: torch.Tensor, cur_ids: torch.Tensor, mask_id
 
 
 # ---- tensor <-> numpy helpers for the storage types (bit moves only) ---------------------------------
+def d3tom_rmsnorm(x: torch.Tensor, gain: torch.Tensor, eps: float, y: torch.Tensor, stream=None) -> None:
+    rows, d = x.shape
+    _check(_lib.d3tom_rmsnorm(_ptr(x), _ptr(gain), rows, d, eps, _ptr(y), _stream(stream)), "d3tom_rmsnorm")
+
+
+def d3tom_rope(q: torch.Tensor, k: torch.Tensor, pos: torch.Tensor, theta: float, stream=None) -> None:
+    rows, H, dh = q.shape
+    assert k.shape == q.shape and pos.dtype == torch.int32 and pos.numel() >= rows
+    _check(_lib.d3tom_rope(_ptr(q), _ptr(k), _ptr(pos), rows, H, dh, theta, _stream(stream)), "d3tom_rope")
+
+
+def _linear_sizes(a, w, epilogue, out, residual):
+    rows, K = a.shape
+    n_w_rows, K2 = w.shape
+    assert K2 == K and a.dtype == torch.bfloat16 and w.dtype == torch.bfloat16 and out.dtype == torch.bfloat16
+    n_out = n_w_rows // 2 if epilogue == D3TOM_LINEAR_SWIGLU else n_w_rows
+    assert out.numel() >= rows * n_out and (residual is None or residual.numel() >= rows * n_out)
+    return rows, n_w_rows, K
+
+
+def d3tom_linear(a: torch.Tensor, w: torch.Tensor, epilogue: int, out: torch.Tensor,
+                 residual: Optional[torch.Tensor] = None, out_chunk: int = 0, stream=None) -> None:
+    rows, n_w_rows, K = _linear_sizes(a, w, epilogue, out, residual)
+    _check(_lib.d3tom_linear(_ptr(a), _ptr(w), rows, n_w_rows, K, epilogue, _ptr(residual), _ptr(out), out_chunk,
+                             _stream(stream)), "d3tom_linear")
+
+
+def d3tom_linear_tile(a: torch.Tensor, w: torch.Tensor, epilogue: int, out: torch.Tensor, tile: int,
+                      residual: Optional[torch.Tensor] = None, out_chunk: int = 0, stream=None) -> None:
+    rows, n_w_rows, K = _linear_sizes(a, w, epilogue, out, residual)
+    _check(_lib.d3tom_linear_tile(_ptr(a), _ptr(w), rows, n_w_rows, K, epilogue, _ptr(residual), _ptr(out), out_chunk,
+                                  tile, _stream(stream)), "d3tom_linear_tile")
+
+
+def block_weights(blocks: Sequence[dict]):
+    """Host array of d3tom_block_weights from dicts of device tensors (keys = field names).  The caller keeps
+    the tensors alive."""
+    arr = (BlockWeights * len(blocks))()
+    for i, b in enumerate(blocks):
+        for name, _ in BlockWeights._fields_:
+            setattr(arr[i], name, b[name].data_ptr())
+    return arr
+
+
+def d3tom_stack_workspace_bytes(N: int, d: int, H: int, F: int, V: int, max_D: int) -> int:
+    return int(_lib.d3tom_stack_workspace_bytes(N, d, H, F, V, max_D))
+
+
+def d3tom_stack_step(x: torch.Tensor, H: int, F: int, blocks, L: int, merge_layer: int, dec_idx: Optional[torch.Tensor],
+                     D: int, vis_start: int, V: int, keep_k: int, mode: int, eps: float, theta: float, y: torch.Tensor,
+                     ws: torch.Tensor, src_pos: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                     kept_idx: Optional[torch.Tensor] = None, assign: Optional[torch.Tensor] = None, stream=None) -> int:
+    """Returns the number of output rows."""
+    N, d = x.shape
+    assert x.dtype == torch.bfloat16 and y.dtype == torch.bfloat16 and y.numel() >= N * d
+    assert src_pos is None or (src_pos.dtype == torch.int32 and src_pos.numel() >= N)
+    assert scores is None or (scores.dtype == torch.float32 and scores.numel() >= V)
+    assert kept_idx is None or (kept_idx.dtype == torch.int32 and kept_idx.numel() >= keep_k)
+    assert assign is None or (assign.dtype == torch.int32 and assign.numel() >= V)
+    n_out = ctypes.c_int(0)
+    _check(_lib.d3tom_stack_step(_ptr(x), N, d, H, F, L, blocks, merge_layer, _ptr(dec_idx), D, vis_start, V, keep_k,
+                                 mode, eps, theta, _ptr(y), _ptr(src_pos), _ptr(scores), _ptr(kept_idx), _ptr(assign),
+                                 ctypes.byref(n_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "d3tom_stack_step")
+    return n_out.value
+
+
 def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
     """float32 numpy array whose values are representable in `dtype` -> device tensor of that type."""
     a = np.ascontiguousarray(a, dtype=np.float32)

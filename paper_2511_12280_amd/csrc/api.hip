@@ -76,7 +76,8 @@ extern "C" int d3tom_profile_kernel_count(void) { return d3tom::prof::NUM_KERNEL
 
 extern "C" const char* d3tom_profile_kernel_name(int kernel) {
     static const char* names[] = {"imp_stats", "imp_scores", "imp_finish", "topk_select", "merge_norms",
-                                  "cos_argmax", "merge_assign", "merge_scatter", "attend", "update_deciders", "cos_reduce"};
+                                  "cos_argmax", "merge_assign", "merge_scatter", "attend", "update_deciders", "cos_reduce",
+                                  "linear", "rmsnorm", "rope", "stack_meta"};
     return (kernel >= 0 && kernel < d3tom::prof::NUM_KERNELS) ? names[kernel] : "";
 }
 

@@ -1,0 +1,119 @@
+// Row-wise pieces of a Llama-style block around the projections: RMSNorm and the rotary position
+// embedding (the blocks that Algorithm 1 runs before and after the merge layer).  Both are pure HBM
+// streaming: one workgroup per token row, 16-byte accesses, float32 arithmetic, one rounding at the store.
+#include "common.hpp"
+
+namespace d3tom {
+
+constexpr int NORM_MAX_CHUNKS = 4;     // 16-byte chunks per thread held in registers: d <= 256 * 4 * 8
+
+// y = x / sqrt(mean(x^2) + eps) * gain
+__global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint16_t* __restrict__ x, const uint16_t* __restrict__ gain,
+                                                           int d, float eps, uint16_t* __restrict__ y) {
+    __shared__ float wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t row = (size_t)blockIdx.x * d;
+    const int nch = d / 8;
+    uint4 v[NORM_MAX_CHUNKS];
+    float ss = 0.f;
+#pragma unroll
+    for (int u = 0; u < NORM_MAX_CHUNKS; ++u) {
+        const int c = tid + u * 256;
+        v[u] = (c < nch) ? *reinterpret_cast<const uint4*>(x + row + (size_t)c * 8) : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int u = 0; u < NORM_MAX_CHUNKS; ++u) {
+        const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { const float a = bf16_lo(w[e]), b = bf16_hi(w[e]); ss += a * a; ss += b * b; }
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) wsum[wave] = ss;
+    __syncthreads();
+    const float total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    const float rinv = 1.0f / sqrtf(total / (float)d + eps);
+#pragma unroll
+    for (int u = 0; u < NORM_MAX_CHUNKS; ++u) {
+        const int c = tid + u * 256;
+        if (c >= nch) continue;
+        const uint4 gq = *reinterpret_cast<const uint4*>(gain + (size_t)c * 8);
+        const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+        const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = pack_bf16x2(bf16_lo(w[e]) * rinv * bf16_lo(gw[e]), bf16_hi(w[e]) * rinv * bf16_hi(gw[e]));
+        *reinterpret_cast<uint4*>(y + row + (size_t)c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
+// Rotary embedding, in place on q and k [rows, H, dh]: channel c < dh/2 of every head is paired with
+// channel c + dh/2 and the pair is turned by pos * theta^(-2c/dh).  The dh/2 angles of a token are the
+// same for all heads and for q and k: the first dh/2 threads evaluate them once, in double precision
+// (positions reach the thousands, where a float32 angle would already be off by 1e-4), the workgroup
+// then streams the row.
+__global__ __launch_bounds__(256) void rope_bf16_kernel(uint16_t* __restrict__ q, uint16_t* __restrict__ k,
+                                                        const int32_t* __restrict__ pos, int H, int dh, double log2_theta) {
+    __shared__ float cs[128], sn[128];
+    const int tid = threadIdx.x;
+    const int half = dh >> 1;
+    const int p = pos[blockIdx.x];
+    if (tid < half) {
+        const double inv_freq = exp2(-2.0 * (double)tid / (double)dh * log2_theta);
+        double s, c;
+        sincos((double)p * inv_freq, &s, &c);
+        cs[tid] = (float)c; sn[tid] = (float)s;
+    }
+    __syncthreads();
+    const int cpp = half / 8;                        // 16-byte chunks per half head
+    const int units = H * cpp;                       // per tensor
+    const size_t row = (size_t)blockIdx.x * H * dh;
+    for (int u = tid; u < 2 * units; u += 256) {
+        uint16_t* t = (u < units) ? q : k;
+        const int uu = (u < units) ? u : u - units;
+        const int h = uu / cpp, cc = uu % cpp;
+        uint16_t* pa = t + row + (size_t)h * dh + cc * 8;
+        const uint4 A = *reinterpret_cast<const uint4*>(pa);
+        const uint4 Bv = *reinterpret_cast<const uint4*>(pa + half);
+        const uint32_t aw[4] = {A.x, A.y, A.z, A.w}, bw[4] = {Bv.x, Bv.y, Bv.z, Bv.w};
+        uint32_t ao[4], bo[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int c0 = cc * 8 + 2 * e;
+            const float a0 = bf16_lo(aw[e]), a1 = bf16_hi(aw[e]), b0 = bf16_lo(bw[e]), b1 = bf16_hi(bw[e]);
+            ao[e] = pack_bf16x2(a0 * cs[c0] - b0 * sn[c0], a1 * cs[c0 + 1] - b1 * sn[c0 + 1]);
+            bo[e] = pack_bf16x2(b0 * cs[c0] + a0 * sn[c0], b1 * cs[c0 + 1] + a1 * sn[c0 + 1]);
+        }
+        *reinterpret_cast<uint4*>(pa) = make_uint4(ao[0], ao[1], ao[2], ao[3]);
+        *reinterpret_cast<uint4*>(pa + half) = make_uint4(bo[0], bo[1], bo[2], bo[3]);
+    }
+}
+
+int rmsnorm_run(const void* x, const void* gain, int rows, int d, float eps, void* y, hipStream_t st) {
+    if (!x || !gain || !y || rows < 1 || d < 1) return D3TOM_ERR_INVALID_ARG;
+    if (!aligned16(x) || !aligned16(gain) || !aligned16(y)) return D3TOM_ERR_INVALID_ARG;
+    if (!(eps >= 0.f)) return D3TOM_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 256 * NORM_MAX_CHUNKS * 8) return D3TOM_ERR_UNSUPPORTED;
+    D3TOM_LAUNCH(RMSNORM, st, (rmsnorm_bf16_kernel<<<rows, 256, 0, st>>>((const uint16_t*)x, (const uint16_t*)gain, d, eps,
+                                                                          (uint16_t*)y)));
+    return D3TOM_OK;
+}
+
+int rope_run(void* q, void* k, const int32_t* pos, int rows, int H, int dh, float theta, hipStream_t st) {
+    if (!q || !k || !pos || rows < 1 || H < 1 || dh < 1) return D3TOM_ERR_INVALID_ARG;
+    if (!aligned16(q) || !aligned16(k)) return D3TOM_ERR_INVALID_ARG;
+    if (!(theta > 1.f) || !(theta < 3.0e38f)) return D3TOM_ERR_INVALID_ARG;
+    if (dh % 16 != 0 || dh > 256) return D3TOM_ERR_UNSUPPORTED;
+    D3TOM_LAUNCH(ROPE, st, (rope_bf16_kernel<<<rows, 256, 0, st>>>((uint16_t*)q, (uint16_t*)k, pos, H, dh, log2((double)theta))));
+    return D3TOM_OK;
+}
+
+}  // namespace d3tom
+
+extern "C" int d3tom_rmsnorm(const void* x, const void* gain, int rows, int d, float eps, void* y, void* stream) {
+    return d3tom::rmsnorm_run(x, gain, rows, d, eps, y, (hipStream_t)stream);
+}
+
+extern "C" int d3tom_rope(void* q, void* k, const int32_t* pos, int rows, int H, int dh, float theta, void* stream) {
+    return d3tom::rope_run(q, k, pos, rows, H, dh, theta, (hipStream_t)stream);
+}

@@ -96,7 +96,7 @@ inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
 namespace prof {
 enum Kernel {
     IMP_STATS = 0, IMP_SCORES, IMP_FINISH, TOPK_SELECT, MERGE_NORMS, COS_ARGMAX, MERGE_ASSIGN, MERGE_SCATTER, ATTEND,
-    UPDATE_DECIDERS, COS_REDUCE,
+    UPDATE_DECIDERS, COS_REDUCE, LINEAR, RMSNORM, ROPE, STACK_META,
     NUM_KERNELS
 };
 extern bool g_enabled;

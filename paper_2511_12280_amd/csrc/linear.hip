@@ -1,0 +1,300 @@
+// d3tom_linear: out = a w^T for the projections of a transformer block (the per-layer 4 n d^2 and 3 n d m
+// terms of the cost model in Section 4.3), bf16 operands, float32 accumulation on MFMA 32x32x16, with the
+// element-wise tail of the projection folded into the epilogue:
+//   PLAIN     out = a w^T, optionally written as several [rows, out_chunk] matrices (q | k | v)
+//   RESIDUAL  out = residual + a w^T                      (the block's two skip connections)
+//   SWIGLU    out = silu(a w_gate^T) * (a w_up^T)         (w holds the F gate rows, then the F up rows)
+// One rounding to bf16, at the store.
+//
+// Workgroup tile: (TM*64) rows x 128 columns of a w^T, 4 waves as 2 x 2, wave tile (TM*32) x 64.  Both
+// operands are contraction-contiguous, so both tiles travel HBM/L2 -> LDS with direct loads (16 bytes per
+// lane, no register staging) into a ring of 64-element k-stages, one s_barrier per stage, the loads of the
+// newest stage spread behind the MFMAs of the current one.  The 16-byte chunk stored at position p of tile
+// row r is chunk p ^ ((r >> 1) & 7), which makes the MFMA operand reads bank-conflict free.
+// For SWIGLU the 128 tile columns are 64 gate rows and the 64 up rows of the same output columns, so the
+// epilogue finds both factors of an output element in the same tile.
+//
+// Workgroup ids are dealt round-robin to the 8 XCDs; each XCD owns a contiguous range of column tiles
+// (its private L2 sees only its share of w) and walks it in panels of a few column tiles, row tile
+// fastest, so that the workgroups running together share operand rows.
+#include "common.hpp"
+#include "direct_load.hpp"
+
+namespace d3tom {
+
+enum { LIN_PLAIN = 0, LIN_RESIDUAL = 1, LIN_SWIGLU = 2 };
+constexpr int LIN_BN = 128;
+constexpr int LIN_BK = 64;
+constexpr int LIN_PAD = 136;      // floats per row of the epilogue staging tile (see the epilogue)
+
+template <int TM> struct LinCfg {
+    static constexpr int BM = TM * 64;
+    static constexpr int NS = (TM == 4) ? 3 : 4;                       // ring stages
+    static constexpr int STAGE = (BM + LIN_BN) * 128;                  // bytes per stage
+    static constexpr int LDS = (NS * STAGE > BM * LIN_PAD * 4) ? NS * STAGE : BM * LIN_PAD * 4;
+};
+
+template <int TM, int EPI>
+__global__ __launch_bounds__(256) void linear_bf16_kernel(
+    const uint16_t* __restrict__ a, const uint16_t* __restrict__ w, int M, int N, int K,
+    const uint16_t* residual, uint16_t* out, int out_chunk, int NRT, int NCT, int cpx, int PC) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    using C = LinCfg<TM>;
+    constexpr int BM = C::BM, NS = C::NS, STAGE = C::STAGE;
+    constexpr int A_LD = BM / 32;                       // direct loads per wave and stage, a tile (8 rows each)
+    constexpr int B_LD = LIN_BN / 32;
+    constexpr int LPS = A_LD + B_LD;
+    extern __shared__ __attribute__((aligned(16))) char ring[];
+
+    // tile of this workgroup
+    const int xcd = blockIdx.x & 7, li = blockIdx.x >> 3;
+    const int panel = li / (NRT * PC), within = li % (NRT * PC);
+    const int cl = panel * PC + within % PC;            // column tile inside this XCD's range
+    const int rt = within / PC, ct = xcd * cpx + cl;
+    if (cl >= cpx || ct >= NCT) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int c = lane & 31, g = lane >> 5;
+    // out columns per tile and rows of w behind the 128 tile columns
+    constexpr int OUT_BN = (EPI == LIN_SWIGLU) ? 64 : 128;
+    const int n_out = (EPI == LIN_SWIGLU) ? N / 2 : N;  // SWIGLU: N counts gate and up rows
+
+    const __amdgpu_buffer_rsrc_t rs_a = make_uniform_rsrc(a, (uint32_t)((size_t)M * K * 2));
+    const __amdgpu_buffer_rsrc_t rs_w = make_uniform_rsrc(w, (uint32_t)((size_t)N * K * 2));
+    // byte offset of this lane inside its operand for each of its direct loads; rows past the end re-read
+    // row 0 (their results are never stored); the k-slice moves through the scalar offset
+    int a_off[A_LD], b_off[B_LD];
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) {
+        const int row = wave * (BM / 4) + i * 8 + (lane >> 3);
+        const int cg = (lane & 7) ^ ((row >> 1) & 7);
+        const int m = rt * BM + row;
+        a_off[i] = ((m < M) ? m : 0) * K * 2 + cg * 16;
+    }
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) {
+        const int row = wave * (LIN_BN / 4) + i * 8 + (lane >> 3);
+        const int cg = (lane & 7) ^ ((row >> 1) & 7);
+        int n;
+        if constexpr (EPI == LIN_SWIGLU) {
+            const int o = ct * 64 + (row & 63);
+            n = (o < n_out) ? o + (row >> 6) * n_out : 0;
+        } else {
+            n = ct * LIN_BN + row;
+            n = (n < N) ? n : 0;
+        }
+        b_off[i] = n * K * 2 + cg * 16;
+    }
+    const int nkt = K / LIN_BK;
+    const uint32_t ring0 = (uint32_t)(size_t)(lds_ptr_t)ring;
+    const uint32_t a_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (BM / 4) * 128);
+    const uint32_t b_lds = __builtin_amdgcn_readfirstlane(ring0 + BM * 128 + wave * (LIN_BN / 4) * 128);
+    auto issue_part = [&](int kt, int stage, int n0, int n1) {
+#pragma unroll
+        for (int i = 0; i < A_LD; ++i)
+            if (i >= n0 && i < n1)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr_t)(size_t)(a_lds + stage * STAGE + i * 8 * 128), 16,
+                                                         a_off[i], kt * (LIN_BK * 2), 0, 0);
+#pragma unroll
+        for (int i = 0; i < B_LD; ++i)
+            if (A_LD + i >= n0 && A_LD + i < n1)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_ptr_t)(size_t)(b_lds + stage * STAGE + i * 8 * 128), 16,
+                                                         b_off[i], kt * (LIN_BK * 2), 0, 0);
+    };
+
+    f32x16 acc[TM][2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    int a_row[TM], b_row[2], a_sw[TM], b_sw[2];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) { const int Rr = wm * (TM * 32) + i * 32 + c; a_row[i] = Rr * 128; a_sw[i] = (Rr >> 1) & 7; }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
+
+    // one stage: feed stage kt to the MFMAs, operand fragments read one k-step ahead; the loads of the
+    // stage NS-1 ahead are issued in four pieces, each right behind a k-step's MFMAs
+    constexpr int LPK = (LPS + 3) / 4;
+    auto stage = [&](int kt, const bool prefetch) {
+        const char* sb = ring + (kt % NS) * STAGE;
+        bf16x8 af[2][TM], bfr[2][2];
+        auto read_frags = [&](int kk, int buf) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+                af[buf][i] = *reinterpret_cast<const bf16x8*>(sb + a_row[i] + (((kk * 2 + g) ^ a_sw[i]) << 4));
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                bfr[buf][j] = *reinterpret_cast<const bf16x8*>(sb + b_row[j] + (((kk * 2 + g) ^ b_sw[j]) << 4));
+        };
+        read_frags(0, 0);
+#pragma unroll
+        for (int kk = 0; kk < LIN_BK / 16; ++kk) {
+            if (kk + 1 < LIN_BK / 16) read_frags(kk + 1, (kk + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
+            if (prefetch) issue_part(kt + NS - 1, (kt + NS - 1) % NS, kk * LPK, min((kk + 1) * LPK, LPS));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+#pragma unroll
+    for (int st = 0; st < NS - 1; ++st)
+        if (st < nkt) issue_part(st, st, 0, LPS);
+    int kt = 0;
+    for (; kt + NS - 1 < nkt; ++kt) {                      // steady state: NS-2 newer stages stay in flight
+        wait_loads_and_barrier<(NS - 2) * LPS>();
+        stage(kt, true);
+    }
+    for (; kt < nkt; ++kt) {                               // drain
+        wait_loads_and_barrier<0>();
+        stage(kt, false);
+    }
+
+    // epilogue: the float32 tile goes through LDS (the ring is free now) so that every thread ends up with
+    // 8 consecutive columns of one row: 16-byte stores, residual rows read the same way.  Rows are padded
+    // to LIN_PAD floats: the two half-waves of an accumulator store (rows 4 apart) then fall into different
+    // bank halves.
+    __syncthreads();
+    float* tile = reinterpret_cast<float*>(ring);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                tile[row * LIN_PAD + wn * 64 + j * 32 + c] = acc[i][j][e];
+            }
+    __syncthreads();
+    constexpr int CG = OUT_BN / 8;                         // 8-column groups per tile row
+    for (int u = tid; u < BM * CG; u += 256) {
+        const int row = u / CG, cg = u % CG;
+        const int m = rt * BM + row, col = ct * OUT_BN + cg * 8;
+        if (m >= M || col >= n_out) continue;
+        const float4 v0 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + cg * 8);
+        const float4 v1 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + cg * 8 + 4);
+        float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        const size_t o = (size_t)(col / out_chunk) * M * out_chunk + (size_t)m * out_chunk + col % out_chunk;
+        if constexpr (EPI == LIN_SWIGLU) {
+            const float4 u0 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + 64 + cg * 8);
+            const float4 u1 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + 64 + cg * 8 + 4);
+            const float up[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = v[e] / (1.f + expf(-v[e])) * up[e];
+        }
+        if constexpr (EPI == LIN_RESIDUAL) {
+            const uint4 r = *reinterpret_cast<const uint4*>(residual + o);
+            const uint32_t rr[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { v[2 * e] += bf16_lo(rr[e]); v[2 * e + 1] += bf16_hi(rr[e]); }
+        }
+        uint4 pk;
+        pk.x = pack_bf16x2(v[0], v[1]); pk.y = pack_bf16x2(v[2], v[3]);
+        pk.z = pack_bf16x2(v[4], v[5]); pk.w = pack_bf16x2(v[6], v[7]);
+        *reinterpret_cast<uint4*>(out + o) = pk;
+    }
+#endif
+}
+
+namespace {
+template <int TM, int EPI>
+int launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out, int out_chunk,
+                  hipStream_t st) {
+    using C = LinCfg<TM>;
+    static bool attr_done = false;       // per instantiation; the attribute only has to be set once per process
+    if (!attr_done) {
+        if (hipFuncSetAttribute((const void*)linear_bf16_kernel<TM, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                C::LDS) != hipSuccess)
+            return D3TOM_ERR_DEVICE;
+        attr_done = true;
+    }
+    const int out_bn = (EPI == LIN_SWIGLU) ? 64 : 128;
+    const int n_out = (EPI == LIN_SWIGLU) ? N / 2 : N;
+    const int NRT = ceil_div(M, C::BM), NCT = ceil_div(n_out, out_bn);
+    const int cpx = ceil_div(NCT, 8);
+    int PC = 32 / NRT;
+    PC = PC < 4 ? 4 : (PC > 16 ? 16 : PC);
+    if (PC > cpx) PC = cpx;
+    const int panels = ceil_div(cpx, PC);
+    const unsigned grid = 8u * (unsigned)(panels * PC * NRT);
+    D3TOM_LAUNCH(LINEAR, st, (linear_bf16_kernel<TM, EPI><<<grid, 256, C::LDS, st>>>(
+        (const uint16_t*)a, (const uint16_t*)w, M, N, K, (const uint16_t*)residual, (uint16_t*)out, out_chunk,
+        NRT, NCT, cpx, PC)));
+    return D3TOM_OK;
+}
+
+template <int EPI>
+int launch_linear_tm(int tm, const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
+                     int out_chunk, hipStream_t st) {
+    switch (tm) {
+        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, st);
+        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, st);
+        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, st);
+    }
+}
+}  // namespace
+
+// Row-tile height for a problem.  Taller tiles move fewer operand bytes per flop (measured throughput of a
+// full machine: 64 rows ~0.75, 128 rows ~0.9 of what 256 rows reach), but the grid runs in whole rounds of
+// 256 workgroups (one per compute unit), so the last, partly filled round can cost more than the tile
+// gains.  Estimated time = rounds * rows per tile / efficiency; the smallest estimate wins, ties go to
+// the smaller tile.
+int linear_pick_tm(int M, int n_tiles_n) {
+    const int cus = 256;
+    const double eff[3] = {0.75, 0.9, 1.0};
+    int best = 1;
+    double best_t = 0.0;
+    for (int i = 0, tm = 1; i < 3; ++i, tm <<= 1) {
+        const long tiles = (long)ceil_div(M, tm * 64) * n_tiles_n;
+        const double t = (double)((tiles + cus - 1) / cus) * tm / eff[i];
+        if (i == 0 || t < best_t - 1e-9) { best = tm; best_t = t; }
+    }
+    return best;
+}
+
+int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, const void* residual, void* out,
+               int out_chunk, int tm_override, hipStream_t st) {
+    if (!a || !w || !out || M < 1 || N < 1 || K < 1) return D3TOM_ERR_INVALID_ARG;
+    if (epilogue < LIN_PLAIN || epilogue > LIN_SWIGLU) return D3TOM_ERR_INVALID_ARG;
+    if (epilogue == LIN_RESIDUAL && !residual) return D3TOM_ERR_INVALID_ARG;
+    if (!aligned16(a) || !aligned16(w) || !aligned16(out) || (residual && !aligned16(residual))) return D3TOM_ERR_INVALID_ARG;
+    if (K % LIN_BK != 0) return D3TOM_ERR_UNSUPPORTED;
+    const int n_out = (epilogue == LIN_SWIGLU) ? N / 2 : N;
+    if (epilogue == LIN_SWIGLU && (N % 2 != 0)) return D3TOM_ERR_INVALID_ARG;
+    if (n_out % 8 != 0) return D3TOM_ERR_UNSUPPORTED;
+    if (out_chunk <= 0) out_chunk = n_out;
+    if (out_chunk % 8 != 0 || n_out % out_chunk != 0) return D3TOM_ERR_INVALID_ARG;
+    if (epilogue != LIN_PLAIN && out_chunk != n_out) return D3TOM_ERR_INVALID_ARG;
+    // 32-bit byte offsets inside each operand
+    if ((size_t)M * K * 2 >= (1ull << 31) || (size_t)N * K * 2 >= (1ull << 31)) return D3TOM_ERR_UNSUPPORTED;
+    const int out_bn = (epilogue == LIN_SWIGLU) ? 64 : 128;
+    int tm = (tm_override == 1 || tm_override == 2 || tm_override == 4) ? tm_override
+                                                                        : linear_pick_tm(M, ceil_div(n_out, out_bn));
+    switch (epilogue) {
+        case LIN_PLAIN: return launch_linear_tm<LIN_PLAIN>(tm, a, w, M, N, K, residual, out, out_chunk, st);
+        case LIN_RESIDUAL: return launch_linear_tm<LIN_RESIDUAL>(tm, a, w, M, N, K, residual, out, out_chunk, st);
+        default: return launch_linear_tm<LIN_SWIGLU>(tm, a, w, M, N, K, residual, out, out_chunk, st);
+    }
+}
+
+}  // namespace d3tom
+
+extern "C" int d3tom_linear(const void* a, const void* w, int rows, int n_w_rows, int K, int epilogue,
+                            const void* residual, void* out, int out_chunk, void* stream) {
+    return d3tom::linear_run(a, w, rows, n_w_rows, K, epilogue, residual, out, out_chunk, 0, (hipStream_t)stream);
+}
+
+// Same as d3tom_linear with the row-tile height fixed (64, 128 or 256 rows: tile = 1, 2, 4); for tuning.
+extern "C" int d3tom_linear_tile(const void* a, const void* w, int rows, int n_w_rows, int K, int epilogue,
+                                 const void* residual, void* out, int out_chunk, int tile, void* stream) {
+    if (tile != 1 && tile != 2 && tile != 4) return D3TOM_ERR_INVALID_ARG;
+    return d3tom::linear_run(a, w, rows, n_w_rows, K, epilogue, residual, out, out_chunk, tile, (hipStream_t)stream);
+}

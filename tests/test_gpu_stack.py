@@ -1,0 +1,349 @@
+"""GPU parity of the blocks around the merge layer and of the whole denoising step (Algorithm 1's loop
+over layers) against the fp64 oracle in oracle/stack.py, through the C ABI.
+
+Tolerances.  Every stored tensor is bf16 on both sides, rounded once from a float32 (GPU) or float64
+(oracle) value.  For a single operation fed with identical inputs the two roundings can differ by one
+bf16 step (2^-8 relative in the worst binade position) when the exact value sits next to a rounding
+boundary, plus the float32 accumulation error of the GPU (<= K * 2^-24 relative to the sum of magnitudes).
+So the single-operation bound is |gpu - ref| <= 2^-7 |ref| + 1e-3 * rms(ref) ("one step").  Through a whole
+stack such one-step differences feed later layers; the bound there is on the relative rms difference and
+on the largest absolute difference, stated with each test.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import stack as OS
+from paper_2511_12280_amd import workloads as W
+import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_12280_amd import binding
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    return binding
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to("cuda").to(torch.bfloat16).contiguous()
+
+
+def _host(t):
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def _one_step(got, ref, what):
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = np.sqrt(np.mean(ref * ref)) + 1e-30
+    excess = np.abs(got - ref) - (2.0 ** -7 * np.abs(ref) + 1e-3 * rms)
+    assert excess.max() <= 0, f"{what}: {np.abs(got - ref).max():.3e} abs, worst excess {excess.max():.3e}"
+    # and nearly all elements agree exactly (same rounding of nearly the same number)
+    same = np.mean(got == ref)
+    assert same > 0.97, f"{what}: only {same:.3f} of the elements are bit-identical"
+
+
+# ---- RMSNorm -----------------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,d", [(1, 8), (37, 256), (5, 1032), (130, 4096), (3, 8192)])
+def test_rmsnorm(B, rows, d):
+    rng = np.random.default_rng([rows, d])
+    x = W.round_to((rng.standard_normal((rows, d)) * rng.uniform(0.1, 30.0, (rows, 1))).astype(np.float32), "bf16")
+    g = W.round_to((1.0 + 0.3 * rng.standard_normal(d)).astype(np.float32), "bf16")
+    y = torch.empty(rows, d, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_rmsnorm(_dev(x), _dev(g), 1e-5, y)
+    torch.cuda.synchronize()
+    _one_step(_host(y), OS.round_bf16(OS.rmsnorm(x, g, 1e-5)), "rmsnorm")
+
+
+def test_rmsnorm_rejects(B):
+    x = torch.zeros(4, 12, dtype=torch.bfloat16, device="cuda")
+    g = torch.ones(12, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_rmsnorm(x, g, 1e-5, x)
+    assert e.value.status == B.D3TOM_ERR_UNSUPPORTED          # row length not a multiple of 8
+    x = torch.zeros(4, 16, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_rmsnorm(x, torch.ones(16, dtype=torch.bfloat16, device="cuda"), -1.0, x)
+    assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+
+
+# ---- rotary embedding --------------------------------------------------------------------------
+@pytest.mark.parametrize("rows,H,dh,theta", [(9, 3, 64, 10000.0), (300, 2, 128, 10000.0), (17, 32, 128, 500000.0),
+                                             (4, 1, 16, 10000.0)])
+def test_rope(B, rows, H, dh, theta):
+    rng = np.random.default_rng([rows, H, dh])
+    q = W.round_to(rng.standard_normal((rows, H, dh)).astype(np.float32), "bf16")
+    k = W.round_to(rng.standard_normal((rows, H, dh)).astype(np.float32), "bf16")
+    pos = np.sort(rng.choice(3773, size=rows, replace=False)).astype(np.int32)
+    pos[0] = 0; pos[-1] = 3772
+    tq, tk = _dev(q), _dev(k)
+    B.d3tom_rope(tq, tk, torch.from_numpy(pos).cuda(), theta)
+    torch.cuda.synchronize()
+    _one_step(_host(tq), OS.round_bf16(OS.rope(q, pos, theta)), "rope q")
+    _one_step(_host(tk), OS.round_bf16(OS.rope(k, pos, theta)), "rope k")
+    np.testing.assert_array_equal(_host(tq)[0], q[0].astype(np.float64))       # position 0 is the identity
+
+
+# ---- projections -------------------------------------------------------------------------------
+LIN_SHAPES = [(5, 128, 64), (64, 128, 128), (200, 384, 256), (493, 512, 1024), (129, 200, 64), (300, 1000, 192),
+              (1000, 256, 4096)]
+
+
+@pytest.mark.parametrize("tile", [1, 2, 4])
+@pytest.mark.parametrize("M,N,K", LIN_SHAPES)
+def test_linear_plain_and_residual(B, M, N, K, tile):
+    rng = np.random.default_rng([M, N, K])
+    a = W.round_to(rng.standard_normal((M, K)).astype(np.float32), "bf16")
+    w = W.round_to((rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32), "bf16")
+    r = W.round_to(rng.standard_normal((M, N)).astype(np.float32), "bf16")
+    ref = OS.linear(a, w)
+    ta, tw, tr = _dev(a), _dev(w), _dev(r)
+    out = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear_tile(ta, tw, B.D3TOM_LINEAR_PLAIN, out, tile)
+    torch.cuda.synchronize()
+    _one_step(_host(out), OS.round_bf16(ref), f"plain {M}x{N}x{K} tile {tile}")
+    B.d3tom_linear_tile(ta, tw, B.D3TOM_LINEAR_RESIDUAL, out, tile, residual=tr)
+    torch.cuda.synchronize()
+    _one_step(_host(out), OS.round_bf16(r.astype(np.float64) + ref), "residual")
+    # in place on the residual buffer
+    B.d3tom_linear_tile(ta, tw, B.D3TOM_LINEAR_RESIDUAL, tr, tile, residual=tr)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_host(tr), _host(out))
+
+
+@pytest.mark.parametrize("M,N,K,chunk", [(77, 384, 128, 128), (493, 768, 256, 256), (10, 48, 64, 16)])
+def test_linear_chunked_output(B, M, N, K, chunk):
+    rng = np.random.default_rng([M, N, K, chunk])
+    a = W.round_to(rng.standard_normal((M, K)).astype(np.float32), "bf16")
+    w = W.round_to((rng.standard_normal((N, K)) / np.sqrt(K)).astype(np.float32), "bf16")
+    ref = OS.round_bf16(OS.linear(a, w))
+    out = torch.zeros(N // chunk, M, chunk, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(_dev(a), _dev(w), B.D3TOM_LINEAR_PLAIN, out, out_chunk=chunk)
+    torch.cuda.synchronize()
+    got = _host(out)
+    for c in range(N // chunk):
+        _one_step(got[c], ref[:, c * chunk:(c + 1) * chunk], f"chunk {c}")
+
+
+@pytest.mark.parametrize("tile", [1, 2, 4])
+@pytest.mark.parametrize("M,F,K", [(5, 64, 64), (200, 96, 128), (493, 704, 256), (130, 1408, 512)])
+def test_linear_swiglu(B, M, F, K, tile):
+    rng = np.random.default_rng([M, F, K])
+    a = W.round_to(rng.standard_normal((M, K)).astype(np.float32), "bf16")
+    w = W.round_to((2.0 * rng.standard_normal((2 * F, K)) / np.sqrt(K)).astype(np.float32), "bf16")
+    ref = OS.round_bf16(OS.swiglu(OS.linear(a, w[:F]), OS.linear(a, w[F:])))
+    out = torch.zeros(M, F, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear_tile(_dev(a), _dev(w), B.D3TOM_LINEAR_SWIGLU, out, tile)
+    torch.cuda.synchronize()
+    _one_step(_host(out), ref, f"swiglu {M}x{F}x{K} tile {tile}")
+
+
+def test_linear_rejects(B):
+    a = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros(16, 64, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(4, 16, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_linear(a, w, B.D3TOM_LINEAR_RESIDUAL, out)                     # residual missing
+    assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_linear(a[:, :32].contiguous(), w[:, :32].contiguous(), B.D3TOM_LINEAR_PLAIN, out)   # K % 64
+    assert e.value.status == B.D3TOM_ERR_UNSUPPORTED
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_linear(a, w, B.D3TOM_LINEAR_PLAIN, out, out_chunk=12)
+    assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_linear_tile(a, w, B.D3TOM_LINEAR_PLAIN, out, 3)
+    assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+
+
+def test_linear_full_size_samples(B):
+    """The projections of the full-size stack (4096 / 11008 wide, 493 and 3773 rows) in the launch
+    configuration the library picks itself; a sample of output elements against float64 dot products."""
+    g = torch.Generator(device="cuda"); g.manual_seed(5)
+    d, F = 4096, 11008
+    for M in (493, 3773):
+        a = torch.randn(M, d, generator=g, device="cuda").to(torch.bfloat16)
+        for name, n_rows, K, epi in (("qkv", 3 * d, d, B.D3TOM_LINEAR_PLAIN), ("gate_up", 2 * F, d, B.D3TOM_LINEAR_SWIGLU),
+                                     ("down", d, F, B.D3TOM_LINEAR_RESIDUAL)):
+            w = (torch.randn(n_rows, K, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+            inp = a if K == d else torch.randn(M, K, generator=g, device="cuda").to(torch.bfloat16)
+            n_out = n_rows // 2 if epi == B.D3TOM_LINEAR_SWIGLU else n_rows
+            res = torch.randn(M, n_out, generator=g, device="cuda").to(torch.bfloat16) if epi == B.D3TOM_LINEAR_RESIDUAL else None
+            out = torch.zeros(M, n_out, dtype=torch.bfloat16, device="cuda")
+            B.d3tom_linear(inp, w, epi, out, residual=res)
+            torch.cuda.synchronize()
+            rng = np.random.default_rng([M, n_rows])
+            rows = np.unique(np.concatenate([[0, M - 1], rng.integers(0, M, 24)]))
+            cols = np.unique(np.concatenate([[0, n_out - 1], rng.integers(0, n_out, 24)]))
+            ah = _host(inp[torch.from_numpy(rows).cuda()])
+            got = _host(out[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+            if epi == B.D3TOM_LINEAR_SWIGLU:
+                wg = _host(w[torch.from_numpy(cols).cuda()]); wu = _host(w[torch.from_numpy(cols + n_out).cuda()])
+                ref = OS.swiglu(OS.linear(ah, wg), OS.linear(ah, wu))
+            else:
+                ref = OS.linear(ah, _host(w[torch.from_numpy(cols).cuda()]))
+                if res is not None:
+                    ref = ref + _host(res[torch.from_numpy(rows).cuda()][:, torch.from_numpy(cols).cuda()])
+            _one_step(got, OS.round_bf16(ref), f"{name} M={M}")
+            del w, out
+
+
+# ---- the whole step ----------------------------------------------------------------------------
+def _gpu_blocks(case):
+    blocks = []
+    for b in case["blocks"]:
+        blocks.append(dict(attn_norm=_dev(b["attn_norm"]), w_qkv=_dev(np.concatenate([b["wq"], b["wk"], b["wv"]], axis=0)),
+                           w_o=_dev(b["wo"]), ffn_norm=_dev(b["ffn_norm"]),
+                           w_gate_up=_dev(np.concatenate([b["w_gate"], b["w_up"]], axis=0)), w_down=_dev(b["w_down"])))
+    return blocks
+
+
+def _run_stack(B, case, keep_k, merge_layer, D=None, mode=0, eps=1e-5, theta=10000.0):
+    N, d, H, F, L, V = case["N"], case["d"], case["H"], case["F"], case["L"], case["V"]
+    D = case["D"] if D is None else D
+    gb = _gpu_blocks(case)
+    arr = B.block_weights(gb)
+    ws = B.workspace(B.d3tom_stack_workspace_bytes(N, d, H, F, V, max(D, 1)))
+    y = torch.zeros(N, d, dtype=torch.bfloat16, device="cuda")
+    src = torch.full((N,), -1, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(V, dtype=torch.float32, device="cuda")
+    kept = torch.zeros(max(keep_k, 1), dtype=torch.int32, device="cuda")
+    asg = torch.zeros(V, dtype=torch.int32, device="cuda")
+    dec = torch.from_numpy(case["dec_idx"][:D].copy()).cuda() if D > 0 else None
+    x = _dev(case["x"])
+    n_out = B.d3tom_stack_step(x, H, F, arr, L, merge_layer, dec, D, case["vis_start"], V, keep_k, mode, eps, theta, y, ws,
+                               src_pos=src, scores=scores, kept_idx=kept, assign=asg)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_host(x), case["x"].astype(np.float64))       # the input is never written
+    return dict(n_out=n_out, y=_host(y[:n_out]), src_pos=src[:n_out].cpu().numpy(), S=scores.cpu().numpy(),
+                kept=kept.cpu().numpy(), assign=asg.cpu().numpy())
+
+
+def _oracle_blocks(case):
+    return [OS.Block(**b) for b in case["blocks"]]
+
+
+STACK_CASES = [
+    # L, d, H, F, P, V, O, D, keep_k, merge_layer
+    (4, 256, 4, 512, 32, 144, 32, 16, 36, 2),          # the tiny configuration's sequence, four blocks
+    (3, 512, 4, 704, 20, 729, 40, 9, 100, 1),          # one crop of visual tokens, head size 128, merge in block 1
+    (3, 256, 2, 320, 7, 300, 21, 5, 299, 3),           # merge in the last block, one token merged away
+    (2, 256, 4, 512, 0, 200, 8, 8, 1, 1),              # no prompt, everything merged into one token
+]
+
+
+def _merge_block_inputs(B, case, l_star, eps=1e-5, theta=10000.0):
+    """What the merge layer of block l_star sees on the GPU: the block's rotated q, k and its post-attention
+    hidden state, rebuilt from the same entry points in the same order (the kernels are deterministic, so
+    these are the very values inside d3tom_stack_step)."""
+    N, d, H, F, V = case["N"], case["d"], case["H"], case["F"], case["V"]
+    dh = d // H
+    x = _dev(case["x"])
+    if l_star > 1:
+        sub = dict(case, L=l_star - 1, blocks=case["blocks"][:l_star - 1])
+        h = _dev(_run_stack(B, sub, 1, 0, D=0)["y"])
+    else:
+        h = x
+    blk = _gpu_blocks(dict(blocks=[case["blocks"][l_star - 1]]))[0]
+    a = torch.empty_like(h)
+    B.d3tom_rmsnorm(h, blk["attn_norm"], eps, a)
+    qkv = torch.empty(3, N, d, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(a, blk["w_qkv"], B.D3TOM_LINEAR_PLAIN, qkv, out_chunk=d)
+    q, k, v = (qkv[i].view(N, H, dh) for i in range(3))
+    pos = torch.arange(N, dtype=torch.int32, device="cuda")
+    B.d3tom_rope(q, k, pos, theta)
+    o = torch.empty(N, H, dh, dtype=torch.bfloat16, device="cuda")
+    cu = torch.tensor([0, N], dtype=torch.int32, device="cuda")
+    B.d3tom_attend(q, k, v, cu, N, 1.0 / np.sqrt(dh), o, B.workspace(256))
+    ht = torch.empty(N, d, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(o.view(N, d), blk["w_o"], B.D3TOM_LINEAR_RESIDUAL, ht, residual=h)
+    torch.cuda.synchronize()
+    return _host(q).astype(np.float32), _host(k).astype(np.float32), _host(ht).astype(np.float32)
+
+
+@pytest.mark.parametrize("L,d,H,F,Pn,V,O,D,keep_k,l_star", STACK_CASES)
+def test_stack_step_against_oracle(B, L, d, H, F, Pn, V, O, D, keep_k, l_star):
+    case = W.stack_case(L * 1000 + V, L=L, d=d, H=H, F=F, P=Pn, V=V, O=O, D=D, std=1.0 / np.sqrt(d), gain_jitter=0.1)
+    got = _run_stack(B, case, keep_k, l_star)
+    assert got["n_out"] == case["N"] - (V - keep_k)
+    # 1. the merge layer inside the stack, stage by stage, on the values the GPU itself fed to it
+    q, k, ht = _merge_block_inputs(B, case, l_star)
+    S_ref = oracle.importance(q, k, case["dec_idx"], case["vis_start"], V)
+    P.check_scores(got["S"], S_ref)
+    slot = np.full(V, -1, np.int32); slot[got["kept"]] = np.arange(keep_k)
+    P.check_kept(got["kept"], slot, S_ref, keep_k)
+    P.check_assign(got["assign"], ht, case["vis_start"], V, got["kept"])
+    # 2. the whole step against the oracle's whole step.  The oracle's own hidden states differ from the
+    # GPU's by single bf16 steps here and there, which moves its scores by up to ~1e-2 relative, so its own
+    # top-k may differ near the threshold: it is told the GPU's (checked) kept set and assignment.
+    ref = OS.stack_step(case["x"], _oracle_blocks(case), H, case["dec_idx"], case["vis_start"], V, keep_k, l_star,
+                        kept_override=got["kept"], assign_override=got["assign"])
+    np.testing.assert_array_equal(got["src_pos"], ref["src_pos"])
+    # Tolerance: a float32 pipeline differs from the float64 one by a few float32 ulps in every value it is
+    # about to store; where that crosses a bf16 rounding boundary the stored value moves by one bf16 step,
+    # and later blocks carry such steps on.  The oracle measures that floor on itself (same step, every
+    # stored value perturbed by 3e-7 relative before rounding); the GPU must stay within 3x of it.
+    alt = OS.stack_step(case["x"], _oracle_blocks(case), H, case["dec_idx"], case["vis_start"], V, keep_k, l_star,
+                        kept_override=got["kept"], assign_override=got["assign"], jitter=3e-7, jitter_seed=1)
+    rms = lambda a, b: np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2))
+    y, yr = got["y"], ref["y"]
+    floor, rel = rms(alt["y"], yr), rms(y, yr)
+    floor_s = (np.abs(alt["S"] - ref["S"]) / np.abs(ref["S"])).max()
+    rel_s = (np.abs(got["S"] - ref["S"]) / np.abs(ref["S"])).max()
+    print(f"stack L={L} d={d}: rel rms {rel:.2e} (floor {floor:.2e}), max abs {np.abs(y - yr).max():.2e} "
+          f"(floor {np.abs(alt['y'] - yr).max():.2e}), score rel {rel_s:.2e} (floor {floor_s:.2e})")
+    assert rel <= 3.0 * floor + 1e-4, (rel, floor)
+    assert np.abs(y - yr).max() <= 3.0 * np.abs(alt["y"] - yr).max() + 2.0 ** -8, np.abs(y - yr).max()
+    assert rel_s <= 3.0 * floor_s + 1e-3, (rel_s, floor_s)
+
+
+def test_stack_step_without_deciders_runs_full_length(B):
+    case = W.stack_case(77, L=3, d=256, H=4, F=512, P=16, V=100, O=12, D=4, std=1.0 / 16, gain_jitter=0.1)
+    got = _run_stack(B, case, 10, 2, D=0)
+    assert got["n_out"] == case["N"]
+    np.testing.assert_array_equal(got["src_pos"], np.arange(case["N"]))
+    ref = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], None, case["vis_start"], case["V"], 10, 2)
+    alt = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], None, case["vis_start"], case["V"], 10, 2, jitter=3e-7)
+    rms = lambda a, b: np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2))
+    assert rms(got["y"], ref["y"]) <= 3.0 * rms(alt["y"], ref["y"]) + 1e-4
+    # keeping every visual token is the same computation: the merge copies rows bit-exactly
+    keep_all = _run_stack(B, case, case["V"], 2)
+    np.testing.assert_array_equal(keep_all["y"], got["y"])
+    np.testing.assert_array_equal(keep_all["src_pos"], got["src_pos"])
+    # a merge layer outside 1 .. L never merges
+    off = _run_stack(B, case, 10, 0)
+    np.testing.assert_array_equal(off["y"], got["y"])
+
+
+def test_stack_step_sum_mode(B):
+    case = W.stack_case(78, L=2, d=256, H=4, F=512, P=8, V=120, O=12, D=6, std=1.0 / 16, gain_jitter=0.1)
+    got = _run_stack(B, case, 30, 1, mode=1)
+    ref = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], case["dec_idx"], case["vis_start"], case["V"], 30, 1,
+                        kept_override=got["kept"], assign_override=got["assign"], mode="sum")
+    alt = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], case["dec_idx"], case["vis_start"], case["V"], 30, 1,
+                        kept_override=got["kept"], assign_override=got["assign"], mode="sum", jitter=3e-7)
+    rms = lambda a, b: np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2))
+    assert rms(got["y"], ref["y"]) <= 3.0 * rms(alt["y"], ref["y"]) + 1e-4
+
+
+def test_stack_step_rejects(B):
+    case = W.stack_case(79, L=1, d=256, H=4, F=512, P=4, V=40, O=4, D=2, std=1.0 / 16)
+    gb = _gpu_blocks(case)
+    arr = B.block_weights(gb)
+    x = _dev(case["x"])
+    y = torch.zeros_like(x)
+    ws = B.workspace(B.d3tom_stack_workspace_bytes(case["N"], 256, 4, 512, 40, 2))
+    dec = torch.from_numpy(case["dec_idx"]).cuda()
+    args = dict(mode=0, eps=1e-5, theta=10000.0, y=y, ws=ws)
+    with pytest.raises(B.D3tomError) as e:       # kept count outside 1 .. V
+        B.d3tom_stack_step(x, 4, 512, arr, 1, 1, dec, 2, 4, 40, 41, **args)
+    assert e.value.status == B.D3TOM_ERR_INVALID_ARG
+    with pytest.raises(B.D3tomError) as e:       # head size the attention kernel is not built for
+        B.d3tom_stack_step(x, 8, 512, arr, 1, 1, dec, 2, 4, 40, 10, **args)
+    assert e.value.status == B.D3TOM_ERR_UNSUPPORTED
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_stack_step(x, 4, 512, arr, 1, 1, dec, 2, 4, 40, 10, mode=0, eps=1e-5, theta=10000.0, y=y, ws=ws[:1024])
+    assert e.value.status == B.D3TOM_ERR_WORKSPACE_TOO_SMALL
