@@ -218,6 +218,81 @@ def run_kv_cache(wl_name: str, steps: int, warmup: int):
                 kernels={k: round(ms * 1e3 / c, 3) for k, (ms, c) in prof.items() if c})
 
 
+def run_stack(traj_repeats: int = 1):
+    """Whole denoising trajectory through the 32-block stack (the full-stack configuration): T steps, each
+    = decider update on the device, embedding of the current response tokens (a row gather, plumbing),
+    d3tom_stack_step.  Step 0 has no deciders and runs unmerged; every later step merges inside block l*.
+    Which response positions are revealed when comes from the synthetic scheduler (no decoding head)."""
+    from paper_2511_12280_amd import binding as B
+    from paper_2511_12280_amd import workloads as W
+    cfg = W.STACK_3645
+    L, d, H, F, P, V, O, T = (cfg[k] for k in ("L", "d", "H", "F", "P", "V", "O", "T"))
+    N = P + V + O
+    keep_k = B.d3tom_keep_count(V, cfg["keep_ratio"])
+    inp = W.stack_device_inputs(cfg)
+    arr = B.block_weights(inp["blocks"])
+    states = torch.from_numpy(np.stack(W.mask_trajectory(cfg["seed"], P + V, O, T, cfg["mask_id"]))).cuda()   # [T+1, N]
+    seq_off = torch.tensor([0, N], dtype=torch.int32, device="cuda")
+    dec_idx = torch.zeros(B.D3TOM_MAX_DECIDERS, dtype=torch.int32, device="cuda")
+    dec_off = torch.zeros(2, dtype=torch.int32, device="cuda")
+    dec_count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = B.workspace(B.d3tom_stack_workspace_bytes(N, d, H, F, V, B.D3TOM_MAX_DECIDERS))
+    x = inp["x"].clone()
+    y = torch.zeros(N, d, dtype=torch.bfloat16, device="cuda")
+    resp = slice(P + V, N)
+
+    def step(s: int) -> int:
+        cur = states[s]
+        D = 0
+        if s > 0:
+            B.d3tom_update_deciders(states[s - 1], cur, cfg["mask_id"], seq_off, B.D3TOM_MAX_DECIDERS, dec_idx, dec_off, dec_count)
+            D = min(int(dec_count.item()), B.D3TOM_MAX_DECIDERS)       # 4 bytes back to the host: the launch sizes need it
+        ids = cur[resp].long()
+        x[resp] = torch.where((ids == cfg["mask_id"])[:, None], inp["mask_vec"][None, :], inp["table"][ids % cfg["table_rows"]])
+        return B.d3tom_stack_step(x, H, F, arr, L, cfg["merge_layer"], dec_idx, D, P, V, keep_k, B.D3TOM_MERGE_MEAN,
+                                  cfg["eps"], cfg["theta"], y, ws)
+
+    step(0); step(1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(traj_repeats):
+        for s in range(T):
+            n_out = step(s)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    def timed(s, reps):
+        torch.cuda.synchronize(); t = time.perf_counter()
+        for _ in range(reps):
+            step(s)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) * 1e3 / reps
+    first_ms, merged_ms = timed(0, 3), timed(T // 2, 8)
+    B.d3tom_profile_enable(True)
+    step(T // 2)
+    torch.cuda.synchronize()
+    prof = B.d3tom_profile_collect()
+    B.d3tom_profile_enable(False)
+    # algorithmic flops of the projections of one merged step: 4 n d^2 + 3 n d F per block part at its length
+    Nm = N - (V - keep_k)
+    l_star = cfg["merge_layer"]
+    attn_proj = lambda n: 2.0 * n * d * 4 * d
+    ffn_proj = lambda n: 2.0 * n * d * 3 * F
+    lin_flops = l_star * attn_proj(N) + (l_star - 1) * ffn_proj(N) + (L - l_star) * attn_proj(Nm) + (L - l_star + 1) * ffn_proj(Nm)
+    lin_ms = prof["linear"][0]
+    tf = lin_flops / (lin_ms * 1e-3) / 1e12
+    return {
+        "workload": f"{cfg['name']}: {L} blocks, hidden {d}, {H}x{d // H} heads, SwiGLU {F}, {V} visual + {P} prompt + {O} response "
+                    f"tokens, merge inside block {l_star} at keep ratio {cfg['keep_ratio']} ({N} -> {Nm} tokens), T={T}",
+        "steps_per_s": round(traj_repeats * T / elapsed, 2), "ms_per_step": round(elapsed * 1e3 / (traj_repeats * T), 3),
+        "first_step_unmerged_ms": round(first_ms, 3), "merged_step_ms": round(merged_ms, 3),
+        "speedup_of_a_merged_step": round(first_ms / merged_ms, 2), "out_rows": int(n_out),
+        "roofline": {"kernel": "linear", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf / PEAK_BF16_TFLOPS, 4), "calls_per_step": prof["linear"][1],
+                     "total_us_per_step": round(lin_ms * 1e3, 1)},
+        "kernels_us_per_step": {k: round(ms * 1e3, 1) for k, (ms, c) in prof.items() if c},
+    }
+
+
 def oracle_baseline(wl, dev):
     """The fp64 oracle, as it stands, on the host cores: whole steps of the workload (all five stages),
     taken evenly over the sweep, until about 12 s of CPU time have been spent."""
@@ -262,6 +337,7 @@ def main():
     ap.add_argument("--workload", default="lavida_3645_sweep")
     ap.add_argument("--also", default="llada_v_1024", help="second workload reported beside the first ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stack", action="store_true", help="skip the full 32-block stack trajectory")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size reference for HBM counters")
     args = ap.parse_args()
@@ -300,6 +376,8 @@ def main():
                                     "merge_layer_us": r2["merge_layer_us"], "attend_us": r2["attend_us"],
                                     "kernels": r2["kernels"]}}
         line["also"]["kv_cache_of_" + args.workload] = run_kv_cache(args.workload, args.steps, args.warmup)
+        if not args.no_stack:
+            line["also"]["denoise_stack_3645"] = run_stack()
     print(json.dumps(line))
 
 

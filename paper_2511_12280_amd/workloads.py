@@ -296,3 +296,39 @@ def stack_case(seed: int, L: int, d: int, H: int, F: int, P: int, V: int, O: int
     is_mask[dec_idx] = False
     x[is_mask] = mask_vec
     return dict(x=round_to(x, "bf16"), blocks=blocks, dec_idx=dec_idx, vis_start=P, V=V, N=N, D=D, H=H, d=d, F=F, L=L)
+
+
+# ----------------------------------------------------------------------------
+# full denoising-step stack (32 Llama-style blocks around the merge layer)
+# ----------------------------------------------------------------------------
+STACK_3645 = dict(name="denoise_stack_3645", L=32, d=4096, H=32, F=11008, P=64, V=3645, O=64, keep_ratio=0.10,
+                  merge_layer=3, T=64, seed=4, std=0.02, eps=1e-5, theta=10000.0, centres=256, crops=5, noise=0.3,
+                  mask_id=126336, table_rows=1024)
+
+
+def stack_device_inputs(cfg: dict, device: str = "cuda") -> dict:
+    """Inputs of the full-size stack, drawn on the device (6.5e9 weights are too many for the host
+    generator): random-init N(0, std) projection weights, unit RMSNorm gains, hidden rows of prompt |
+    clustered visual tokens (per crop: `centres` cluster centres + N(0, noise)) | response, an embedding
+    table for revealed response tokens and the one [MASK] embedding.  bf16 throughout."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(cfg["seed"])
+    d, F, L = cfg["d"], cfg["F"], cfg["L"]
+    P, V, O = cfg["P"], cfg["V"], cfg["O"]
+
+    def rnd(*shape, std=1.0):
+        return (torch.randn(*shape, generator=g, device=device) * std).to(torch.bfloat16)
+
+    ones = lambda: torch.ones(d, dtype=torch.bfloat16, device=device)
+    blocks = [dict(attn_norm=ones(), w_qkv=rnd(3 * d, d, std=cfg["std"]), w_o=rnd(d, d, std=cfg["std"]), ffn_norm=ones(),
+                   w_gate_up=rnd(2 * F, d, std=cfg["std"]), w_down=rnd(d, F, std=cfg["std"])) for _ in range(L)]
+    x = rnd(P + V + O, d)
+    per = V // cfg["crops"]
+    for c in range(cfg["crops"]):
+        lo = P + c * per
+        hi = P + V if c == cfg["crops"] - 1 else lo + per
+        cen = rnd(cfg["centres"], d).float()
+        pick = torch.randint(0, cfg["centres"], (hi - lo,), generator=g, device=device)
+        x[lo:hi] = (cen[pick] + cfg["noise"] * torch.randn(hi - lo, d, generator=g, device=device)).to(torch.bfloat16)
+    return dict(blocks=blocks, x=x, table=rnd(cfg["table_rows"], d), mask_vec=rnd(d))
