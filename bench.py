@@ -338,6 +338,8 @@ def main():
     ap.add_argument("--also", default="llada_v_1024", help="second workload reported beside the first ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stack", action="store_true", help="skip the full 32-block stack trajectory")
+    ap.add_argument("--stack-only", action="store_true",
+                    help="run only the 32-block stack trajectory and print its record (for profiling that part alone)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size reference for HBM counters")
     args = ap.parse_args()
@@ -353,6 +355,9 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
         del a, b
+    if args.stack_only:
+        print(json.dumps(run_stack()))
+        return
     wl, res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
     dom = res["kernels"][res["dominant"]]
     line = {
