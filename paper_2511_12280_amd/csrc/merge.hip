@@ -113,7 +113,8 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 }
 
 // ---- cosine GEMM + fused argmax, bf16 MFMA ---------------------------------------------------
-// Workgroup tile: (TM*64) pruned rows x 128 kept slots, 4 waves as 2 x 2, wave tile (TM*32) x 64.
+// Workgroup tile: (TM*64) pruned rows x 128 kept slots; waves 0..3 compute (2 x 2, wave tile (TM*32) x 64),
+// waves 4..7 only issue the loads.
 //
 // Operand tiles go HBM/L2 -> LDS with direct loads (buffer_load ... lds, 16 bytes per lane, no register
 // staging) into a ring of COS_NS stages of 64 contraction elements; the loads of stage kt+3 are in
@@ -130,7 +131,7 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 constexpr int COS_NS = 4;
 
 template <int TM>
-__global__ __launch_bounds__(256) void cos_argmax_bf16(
+__global__ __launch_bounds__(512) void cos_argmax_bf16(
     const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
@@ -151,7 +152,8 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     if (rt * BM >= s.M || ct * COS_BN >= s.k) return;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = (tid >> 6) & 3, lane = tid & 63;
+    const bool loader = tid >> 8;                          // waves 4..7 only move data, waves 0..3 only compute
     const int wm = wave >> 1, wn = wave & 1;
     const int c = lane & 31, g = lane >> 5;
     const int32_t* pr = pruned + (size_t)b * max_V;
@@ -179,7 +181,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         const int j = min(max(kp[(r < s.k) ? r : 0], 0), s.V - 1);
         b_off[i] = j * d * 2 + cg * 16;
     }
-    for (int t = tid; t < COS_BN; t += 256) {
+    for (int t = tid; t < COS_BN; t += 512) {
         const int r = ct * COS_BN + t;
         rnB[t] = (r < s.k) ? rn[r] : 0.f;
     }
@@ -221,11 +223,8 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
     for (int j = 0; j < 2; ++j) { const int Rr = wn * 64 + j * 32 + c; b_row[j] = BM * 128 + Rr * 128; b_sw[j] = (Rr >> 1) & 7; }
 
-    // one stage: (optionally) start the loads of the stage COS_NS-1 ahead, then feed stage kt to the MFMAs
-    // The loads of the stage COS_NS-1 ahead are spread over the four k-steps, each piece right behind that
-    // step's MFMAs, so that their scalar set-up issues while the matrix pipe is busy.
-    constexpr int LPK = (LPS + 3) / 4;
-    auto stage = [&](int kt, const bool prefetch) {
+    // one stage: feed stage kt to the MFMAs
+    auto stage = [&](int kt) {
         const char* sb = ring + (kt % COS_NS) * STAGE;
         // operand fragments are read one k-step ahead of the MFMAs that use them, so the LDS latency
         // of step kk + 1 is covered by the matrix work of step kk
@@ -248,21 +247,27 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[kk & 1][i], bfr[kk & 1][j], acc[i][j], 0, 0, 0);
-            if (prefetch) issue_part(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS, kk * LPK, min((kk + 1) * LPK, LPS));
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // A wave that issues a direct load waits for room in the CU's vector-memory queue; in a computing wave
+    // that wait stalls the MFMA stream, so the loads have waves of their own.  One s_barrier per stage:
+    // the loaders arrive once stage kt has landed, the consumers once they are done with stage kt-1,
+    // whose slot the loaders then refill with stage kt+COS_NS-1.
+    if (loader) {
 #pragma unroll
-    for (int st = 0; st < COS_NS - 1; ++st)
-        if (st < nkt) issue(st, st);
-    int kt = 0;
-    for (; kt + COS_NS - 1 < nkt; ++kt) {                  // steady state: COS_NS-2 newer stages stay in flight
-        wait_loads_and_barrier<(COS_NS - 2) * LPS>();
-        stage(kt, true);
-    }
-    for (; kt < nkt; ++kt) {                               // drain
-        wait_loads_and_barrier<0>();
-        stage(kt, false);
+        for (int st = 0; st < COS_NS - 1; ++st)
+            if (st < nkt) issue(st, st);
+        for (int kt = 0; kt < nkt; ++kt) {
+            if (kt + COS_NS - 2 <= nkt - 1) wait_loads_and_barrier<(COS_NS - 2) * LPS>();
+            else wait_loads_and_barrier<0>();
+            if (kt + COS_NS - 1 < nkt) issue(kt + COS_NS - 1, (kt + COS_NS - 1) % COS_NS);
+        }
+    } else {
+        for (int kt = 0; kt < nkt; ++kt) {
+            wait_loads_and_barrier<0>();
+            stage(kt);
+        }
     }
 
     if (ksplit > 1) {
@@ -270,6 +275,7 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
         const int tile_id = (b * nrt_launch + rt) * nct_launch + ct;
         const int n_tiles = (int)(gridDim.x / (8 * R * C)) * nrt_launch * nct_launch;
         float* blk = dots + ((size_t)blockIdx.y * n_tiles + tile_id) * (BM * COS_BN);
+        if (loader) return;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -305,15 +311,17 @@ __global__ __launch_bounds__(256) void cos_argmax_bf16(
     // order.  Rows are padded to 33 entries so that the scan of 32 different rows hits 32 different banks.
     __syncthreads();                                           // all waves are done with the ring
     float2* cand = reinterpret_cast<float2*>(ring);            // [BM][2][33]
+    if (!loader) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-            cand[(row * 2 + wn) * 33 + c] = make_float2(bv[i][e], __int_as_float(bi[i][e]));
-        }
+            for (int e = 0; e < 16; ++e) {
+                const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
+                cand[(row * 2 + wn) * 33 + c] = make_float2(bv[i][e], __int_as_float(bi[i][e]));
+            }
+    }
     __syncthreads();
-    for (int t = tid; t < BM * 2; t += 256) {
+    for (int t = tid; t < BM * 2; t += 512) {
         const int row = t >> 1, half = t & 1;                  // half 0: slots of wave column 0 (lower slots)
         const float2* cr = cand + (row * 2 + half) * 33;
         float best = -INFINITY; int bidx = 0x7FFFFFFF;
@@ -748,11 +756,11 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         float* dots = (float*)(wsb + w.dots_off);
         const size_t lds = (size_t)COS_NS * (BM + COS_BN) * 128;
         if (TM == 1)
-            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 256, lds, st>>>(
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
                 rnorm, w.NCT, part, XC, R, C, ksplit, dots, nrt, nct));
         else
-            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 256, lds, st>>>(
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
                 rnorm, w.NCT, part, XC, R, C, 1, dots, nrt, nct));
         if (split) {
