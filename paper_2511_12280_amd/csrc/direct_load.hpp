@@ -20,15 +20,10 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_uniform_rsrc(const void* 
 
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
-    // N direct loads of this wave may stay in flight; everything older has landed in LDS
-    if constexpr (N == 16) asm volatile("s_waitcnt vmcnt(16) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if constexpr (N == 12) asm volatile("s_waitcnt vmcnt(12) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if constexpr (N == 8) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else if constexpr (N == 6) asm volatile("s_waitcnt vmcnt(6) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    else {
-        static_assert(N == 0, "add the wait count");
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    }
+    // N vector-memory operations of this wave may stay in flight (at most 63: the counter has 6 bits);
+    // everything older has landed in LDS
+    static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
 }  // namespace d3tom

@@ -251,14 +251,16 @@ int launch_linear_tm(int tm, const void* a, const void* w, int M, int N, int K, 
 }
 }  // namespace
 
-// Row-tile height for a problem.  Taller tiles move fewer operand bytes per flop (measured throughput of a
-// full machine: 64 rows ~0.75, 128 rows ~0.9 of what 256 rows reach), but the grid runs in whole rounds of
-// 256 workgroups (one per compute unit), so the last, partly filled round can cost more than the tile
-// gains.  Estimated time = rounds * rows per tile / efficiency; the smallest estimate wins, ties go to
-// the smaller tile.
+// Row-tile height for a problem.  Taller tiles move fewer operand bytes per flop, and fewer workgroups then
+// share (and ask at the same moment for) the same rows of w, which matters when w comes cold from HBM, as a
+// block's weights do (read once per step).  Measured per-flop throughput of a full machine with cold weights:
+// 64 rows 0.55, 128 rows 0.72 of what 256 rows reach (0.75 / 0.92 with w resident in the memory-side cache).
+// But the grid runs in whole rounds of 256 workgroups (one per compute unit), so a partly filled last
+// round can cost more than the tile gains.  Estimated time = rounds * rows per tile / efficiency; the
+// smallest estimate wins, ties go to the smaller tile.
 int linear_pick_tm(int M, int n_tiles_n) {
     const int cus = 256;
-    const double eff[3] = {0.75, 0.92, 1.0};
+    const double eff[3] = {0.55, 0.72, 1.0};
     int best = 1;
     double best_t = 0.0;
     for (int i = 0, tm = 1; i < 3; ++i, tm <<= 1) {
