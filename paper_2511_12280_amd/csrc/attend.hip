@@ -294,6 +294,227 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
         }
 #endif
 }
+// ---- short sequences: the keys are split across the four waves -------------------------------------
+// With a few hundred keys the kernel above is one short serial chain per workgroup (8 stages at 493 keys)
+// on half of the CUs.  Here a workgroup owns 32 queries of one head and its four waves take the 32-key
+// tiles w, w + 4, w + 8, ... with the same transposed products as above; each wave has a private K and V
+// tile in LDS, filled by its own direct loads, so the waves never meet inside the loop (no s_barrier, only
+// waits for the wave's own loads: K of the next tile is requested as soon as the K fragments are in
+// registers, V of the next tile as soon as the V fragments are).  At the end the four partial results
+// (running max, sum, O^T) meet in LDS and wave t combines and stores the 32 output dims t*32 ..
+// Four times the K/V traffic per query of the kernel above, which is why it is only used while the whole
+// sample is short.
+constexpr int ATS_BK = 32;      // keys per wave tile
+constexpr int ATS_MAX_KEYS = 512;
+
+template <int N>
+__device__ __forceinline__ void att_wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <int DH>
+__global__ __launch_bounds__(256, 2) void attend_bf16_short_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int KS = DH / 16;
+    constexpr int DT = DH / 32;
+    constexpr int ROWB = DH * 2;
+    constexpr int NCHK = DH / 8;
+    constexpr int RPI = 64 / NCHK;              // rows per wave-wide direct load
+    constexpr int LD = ATS_BK / RPI;            // direct loads per operand tile
+    constexpr int TILE = ATS_BK * ROWB;         // bytes of one K (or V) tile
+    constexpr int WREG = 2 * TILE;              // bytes of a wave's private region (K tile, V tile)
+    static_assert(WREG == DT * 16 * 64 * 4, "a wave's region also holds its partial O^T");
+    extern __shared__ __attribute__((aligned(16))) char ring[];
+    __shared__ float part_m[4][32], part_l[4][32];
+
+    const int xcd = blockIdx.x & 7, li = blockIdx.x >> 3;
+    const int hb = (li / nqt) * 8 + xcd, qt = li % nqt;
+    if (hb >= H * nB) return;
+    const int h = hb % H, b = hb / H;
+    const int tok0 = cu[b];
+    const int n = cu[b + 1] - tok0;
+    if (qt * 32 >= n) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int c = lane & 31, g = lane >> 5;
+    const size_t rs = (size_t)H * DH;
+    const uint16_t* kb = k + (size_t)tok0 * rs + (size_t)h * DH;
+    const uint16_t* vb = v + (size_t)tok0 * rs + (size_t)h * DH;
+    const uint32_t span = (uint32_t)(((size_t)(n - 1) * rs + DH) * 2);      // rows past the end load as zeros
+    const __amdgpu_buffer_rsrc_t rk = att_uniform_rsrc(kb, span), rv = att_uniform_rsrc(vb, span);
+    const int row_bytes = (int)(rs * 2);
+
+    const int qrow = qt * 32 + c;
+    const bool qvalid = qrow < n;
+    bf16x8 qf[KS];
+    {
+        const uint16_t* qp = q + (size_t)(tok0 + (qvalid ? qrow : 0)) * rs + (size_t)h * DH + g * 8;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) {
+            bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+            qf[kk] = qvalid ? *reinterpret_cast<const bf16x8*>(qp + kk * 16) : z;
+        }
+    }
+    f32x16 ot[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) ot[t][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    // direct loads of a 32-key tile: same chunk swizzles as in the kernel above
+    const int ld_pos = lane % NCHK;
+    int k_off[LD], v_off[LD];
+#pragma unroll
+    for (int i = 0; i < LD; ++i) {
+        const int r = lane / NCHK + i * RPI;
+        k_off[i] = r * row_bytes + (((ld_pos ^ (r & 15)) & (NCHK - 1)) << 4);
+        v_off[i] = r * row_bytes + (((ld_pos ^ ((r & 3) * 4)) & (NCHK - 1)) << 4);
+    }
+    char* wreg = ring + wave * WREG;
+    const uint32_t wave_lds = __builtin_amdgcn_readfirstlane((uint32_t)(size_t)(att_lds_ptr_t)ring + wave * WREG);
+    auto issue_k = [&](int key0) {
+        const int kofs = key0 * row_bytes;
+#pragma unroll
+        for (int i = 0; i < LD; ++i) att_direct_load(rk, k_off[i] + kofs, wave_lds + i * RPI * ROWB);
+    };
+    auto issue_v = [&](int key0) {
+        const int kofs = key0 * row_bytes;
+#pragma unroll
+        for (int i = 0; i < LD; ++i) att_direct_load(rv, v_off[i] + kofs, wave_lds + TILE + i * RPI * ROWB);
+    };
+    int k_addr[KS];
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) k_addr[kk] = c * ROWB + ((((kk * 2 + g) ^ (c & 15)) & (NCHK - 1)) << 4);
+    const int tr_j = (lane & 15) >> 2, tr_t = lane & 3, tr_half = (lane >> 4) & 1;
+    int v_addr[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) {
+        const int chunk = t * 4 + tr_half * 2 + (tr_t >> 1);
+        v_addr[t] = TILE + (g * 4 + tr_j) * ROWB + (tr_t % 2) * 8 + (((chunk ^ (tr_j * 4)) & (NCHK - 1)) << 4);
+    }
+
+    const int ntile = (n + ATS_BK - 1) / ATS_BK;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) asm volatile("" :: "v"(qf[kk]));      // Q has arrived before the first direct load
+    if (wave < ntile) { issue_k(wave * ATS_BK); issue_v(wave * ATS_BK); }
+    for (int it = wave; it < ntile; it += 4) {
+        const int key0 = it * ATS_BK;
+        const bool more = it + 4 < ntile;
+        att_wait_loads<LD>();                                  // K of this tile has landed (V may still be on its way)
+        bf16x8 kf[KS];
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(wreg + k_addr[kk]);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 st;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[e] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KS; ++kk) st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], st, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        // the K fragments are in registers (the MFMAs above consumed them): the K tile is free
+        if (more) issue_k(key0 + 4 * ATS_BK);
+        __builtin_amdgcn_sched_barrier(0);
+        if (key0 + ATS_BK > n) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int key = key0 + (e >> 2) * 8 + g * 4 + (e & 3);
+                if (key >= n) st[e] = -INFINITY;
+            }
+        }
+        float tmax = st[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, st[e]);
+        tmax = att_pair_max(tmax);
+        const float m_new = fmaxf(m_run, tmax);                // finite: every tile holds >= 1 valid key
+        const float ms = m_new * scale2;
+        float psum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale2, -ms));
+            st[e] = p;
+            psum += p;
+        }
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+            l_run *= alpha;
+#pragma unroll
+            for (int t = 0; t < DT; ++t)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
+        }
+        l_run += psum;
+        m_run = m_new;
+        __builtin_amdgcn_sched_barrier(0);
+        // V of this tile: everything older than the K loads just issued has landed
+        if (more) att_wait_loads<LD>(); else att_wait_loads<0>();
+        att_short4 vf[2][DT][2];
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                const char* pa = wreg + v_addr[t] + hh * 16 * ROWB;
+                vf[hh][t][0] = lds_read_tr16(pa);
+                vf[hh][t][1] = lds_read_tr16(pa + 8 * ROWB);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            bf16x8 pf;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) pf[j] = (__bf16)st[hh * 8 + j];
+#pragma unroll
+            for (int t = 0; t < DT; ++t) {
+                typedef __attribute__((__vector_size__(8 * sizeof(short)))) short att_short8;
+                const att_short8 v8 = __builtin_shufflevector(vf[hh][t][0], vf[hh][t][1], 0, 1, 2, 3, 4, 5, 6, 7);
+                ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, v8), pf, ot[t], 0, 0, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        // the V fragments are in registers: the V tile is free
+        if (more) issue_v(key0 + 4 * ATS_BK);
+    }
+    // the four partial results meet in LDS (every wave's own region is free: it has no load in flight)
+    l_run = att_pair_sum(l_run);
+    float* po = reinterpret_cast<float*>(wreg);
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) po[(t * 16 + e) * 64 + lane] = ot[t][e];
+    if (g == 0) { part_m[wave][c] = m_run; part_l[wave][c] = l_run; }
+    __syncthreads();
+    if (wave >= DT || !qvalid) return;
+    float m = part_m[0][c];
+#pragma unroll
+    for (int w2 = 1; w2 < 4; ++w2) m = fmaxf(m, part_m[w2][c]);
+    float f[4], l = 0.f;
+#pragma unroll
+    for (int w2 = 0; w2 < 4; ++w2) {
+        const float mw = part_m[w2][c];
+        f[w2] = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mw - m) * scale2);
+        l += part_l[w2][c] * f[w2];
+    }
+    const float inv = 1.0f / l;
+    float acc[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        float a2 = 0.f;
+#pragma unroll
+        for (int w2 = 0; w2 < 4; ++w2)
+            a2 += reinterpret_cast<const float*>(ring + w2 * WREG)[(wave * 16 + e) * 64 + lane] * f[w2];
+        acc[e] = a2 * inv;
+    }
+    uint16_t* op = o + (size_t)(tok0 + qrow) * rs + (size_t)h * DH + wave * 32;
+#pragma unroll
+    for (int e4 = 0; e4 < 4; ++e4) {
+        uint2 w2;
+        w2.x = pack_bf16x2(acc[e4 * 4 + 0], acc[e4 * 4 + 1]);
+        w2.y = pack_bf16x2(acc[e4 * 4 + 2], acc[e4 * 4 + 3]);
+        *reinterpret_cast<uint2*>(op + e4 * 8 + g * 4) = w2;
+    }
+#endif
+}
+
 // generic: one workgroup per (query, head), keys in chunks of 256, plain float online softmax
 template <typename T>
 __global__ __launch_bounds__(256) void attend_generic_kernel(
@@ -362,7 +583,29 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
     const float scale2 = scale * LOG2E;
     // the tiled kernel addresses one sample's K / V rows with 32-bit byte offsets
     const bool fits32 = ((size_t)max_seqlen + ATT_BK) * (size_t)H * (size_t)dh * 2 < ((size_t)1 << 31);
-    if (dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32) {
+    // short samples and too few 128-query tiles to fill the chip: keys split across the waves (measured
+    // crossover with the tiled kernel: ~550 keys at 32 heads)
+    if (dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32 && max_seqlen <= ATS_MAX_KEYS &&
+        (long)ceil_div(max_seqlen, ATT_BQ) * H * B <= 512) {
+        const int nqt = ceil_div(max_seqlen, 32);
+        const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
+        const size_t lds = (size_t)4 * 2 * ATS_BK * dh * 2;
+        static bool attr_set_s = false;
+        if (!attr_set_s) {
+            if (hipFuncSetAttribute((const void*)attend_bf16_short_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    4 * 2 * ATS_BK * 128 * 2) != hipSuccess ||
+                hipFuncSetAttribute((const void*)attend_bf16_short_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    4 * 2 * ATS_BK * 64 * 2) != hipSuccess)
+                return D3TOM_ERR_DEVICE;
+            attr_set_s = true;
+        }
+        if (dh == 128)
+            D3TOM_LAUNCH(ATTEND, st, attend_bf16_short_kernel<128><<<g, 256, lds, st>>>(
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
+        else
+            D3TOM_LAUNCH(ATTEND, st, attend_bf16_short_kernel<64><<<g, 256, lds, st>>>(
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
+    } else if (dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32) {
         const int nqt = ceil_div(max_seqlen, ATT_BQ);
         const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)ATT_NS * 2 * ATT_BK * dh * 2;

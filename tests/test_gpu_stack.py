@@ -58,6 +58,16 @@ def test_rmsnorm(B, rows, d):
     _one_step(_host(y), OS.round_bf16(OS.rmsnorm(x, g, 1e-5)), "rmsnorm")
 
 
+def test_rmsnorm_in_place(B):
+    rng = np.random.default_rng(3)
+    x = W.round_to(rng.standard_normal((50, 512)).astype(np.float32), "bf16")
+    g = W.round_to((1.0 + 0.3 * rng.standard_normal(512)).astype(np.float32), "bf16")
+    t = _dev(x)
+    B.d3tom_rmsnorm(t, _dev(g), 1e-6, t)
+    torch.cuda.synchronize()
+    _one_step(_host(t), OS.round_bf16(OS.rmsnorm(x, g, 1e-6)), "rmsnorm in place")
+
+
 def test_rmsnorm_rejects(B):
     x = torch.zeros(4, 12, dtype=torch.bfloat16, device="cuda")
     g = torch.ones(12, dtype=torch.bfloat16, device="cuda")
@@ -72,7 +82,7 @@ def test_rmsnorm_rejects(B):
 
 # ---- rotary embedding --------------------------------------------------------------------------
 @pytest.mark.parametrize("rows,H,dh,theta", [(9, 3, 64, 10000.0), (300, 2, 128, 10000.0), (17, 32, 128, 500000.0),
-                                             (4, 1, 16, 10000.0)])
+                                             (4, 1, 16, 10000.0), (6, 2, 256, 10000.0)])
 def test_rope(B, rows, H, dh, theta):
     rng = np.random.default_rng([rows, H, dh])
     q = W.round_to(rng.standard_normal((rows, H, dh)).astype(np.float32), "bf16")
@@ -88,7 +98,7 @@ def test_rope(B, rows, H, dh, theta):
 
 
 # ---- projections -------------------------------------------------------------------------------
-LIN_SHAPES = [(5, 128, 64), (64, 128, 128), (200, 384, 256), (493, 512, 1024), (129, 200, 64), (300, 1000, 192),
+LIN_SHAPES = [(1, 8, 64), (5, 128, 64), (64, 128, 128), (200, 384, 256), (493, 512, 1024), (129, 200, 64), (300, 1000, 192),
               (1000, 256, 4096)]
 
 
