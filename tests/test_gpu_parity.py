@@ -133,6 +133,18 @@ def test_attend_varlen(H, dh, dtype):
         check_attend(o, q, k, v, dtype)
 
 
+@pytest.mark.parametrize("longest", [512, 513])
+@pytest.mark.parametrize("H,dh", [(5, 128), (3, 64)])
+def test_attend_both_sides_of_the_short_sample_limit(H, dh, longest):
+    """Up to 512 keys per sample the keys are split across the waves of a workgroup; one key more and the
+    tiled kernel takes the whole batch, short samples included."""
+    lens = [1, 31, 32, 33, 97, 129, longest]
+    qkv = [W.random_qkv(700 + n, n, H, dh, "bf16") for n in lens]
+    outs = gpu_attend(qkv, "bf16")
+    for (q, k, v), o in zip(qkv, outs):
+        check_attend(o, q, k, v, "bf16")
+
+
 def test_attend_special_cases_bf16():
     q, k, v = W.random_qkv(5, 150, 2, 128, "bf16", spread=2.0)
     v1 = np.broadcast_to(v[:1], v.shape).copy()
