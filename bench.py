@@ -280,12 +280,17 @@ def run_stack(traj_repeats: int = 1):
     lin_flops = l_star * attn_proj(N) + (l_star - 1) * ffn_proj(N) + (L - l_star) * attn_proj(Nm) + (L - l_star + 1) * ffn_proj(Nm)
     lin_ms = prof["linear"][0]
     tf = lin_flops / (lin_ms * 1e-3) / 1e12
+    # the paper's cost model (Section 4.3) for the same step: its l* counts the full layers before the split one
+    alpha = 1.0 - keep_k / V
+    mf = lambda a, T_: B.d3tom_model_flops(a, l_star - 1, L, T_, V, P, O, d, F)
+    model_full, model_merged = mf(0.0, 1), mf(alpha, 2) - mf(alpha, 1)
     return {
         "workload": f"{cfg['name']}: {L} blocks, hidden {d}, {H}x{d // H} heads, SwiGLU {F}, {V} visual + {P} prompt + {O} response "
                     f"tokens, merge inside block {l_star} at keep ratio {cfg['keep_ratio']} ({N} -> {Nm} tokens), T={T}",
         "steps_per_s": round(traj_repeats * T / elapsed, 2), "ms_per_step": round(elapsed * 1e3 / (traj_repeats * T), 3),
         "first_step_unmerged_ms": round(first_ms, 3), "merged_step_ms": round(merged_ms, 3),
-        "speedup_of_a_merged_step": round(first_ms / merged_ms, 2), "out_rows": int(n_out),
+        "speedup_of_a_merged_step": round(first_ms / merged_ms, 2),
+        "cost_model_flops_ratio_unmerged_over_merged": round(model_full / model_merged, 2), "out_rows": int(n_out),
         "roofline": {"kernel": "linear", "bound": "mfma", "achieved": round(tf, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf / PEAK_BF16_TFLOPS, 4), "calls_per_step": prof["linear"][1],
                      "total_us_per_step": round(lin_ms * 1e3, 1)},

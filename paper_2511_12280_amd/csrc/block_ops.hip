@@ -47,6 +47,62 @@ __global__ __launch_bounds__(256) void rmsnorm_bf16_kernel(const uint16_t* __res
     }
 }
 
+// h = residual + sum of the float32 partial products of a split projection, rounded once to bf16 and stored;
+// when a gain is given, also y = rmsnorm(h) of the stored (rounded) values: the normalisation that opens the
+// next sub-block, so that it needs no launch of its own.  Slices are added in ascending order.
+__global__ __launch_bounds__(256) void add_norm_bf16_kernel(const float* __restrict__ part, int nsplit, size_t split_stride,
+                                                            const uint16_t* residual, const uint16_t* __restrict__ gain,
+                                                            int d, float eps, uint16_t* h, uint16_t* __restrict__ y) {
+    __shared__ float wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const size_t row = (size_t)blockIdx.x * d;
+    const int nch = d / 8;
+    uint32_t hv[NORM_MAX_CHUNKS][4];
+    float ss = 0.f;
+#pragma unroll
+    for (int u = 0; u < NORM_MAX_CHUNKS; ++u) {
+        const int c = tid + u * 256;
+        if (c >= nch) { hv[u][0] = hv[u][1] = hv[u][2] = hv[u][3] = 0; continue; }
+        const uint4 r = *reinterpret_cast<const uint4*>(residual + row + (size_t)c * 8);
+        const uint32_t rr[4] = {r.x, r.y, r.z, r.w};
+        float acc[8];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { acc[2 * e] = bf16_lo(rr[e]); acc[2 * e + 1] = bf16_hi(rr[e]); }
+        float sum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int s = 0; s < nsplit; ++s) {
+            const float* p = part + (size_t)s * split_stride + row + (size_t)c * 8;
+            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+            sum[0] += a.x; sum[1] += a.y; sum[2] += a.z; sum[3] += a.w;
+            sum[4] += b.x; sum[5] += b.y; sum[6] += b.z; sum[7] += b.w;
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            hv[u][e] = pack_bf16x2(acc[2 * e] + sum[2 * e], acc[2 * e + 1] + sum[2 * e + 1]);
+            const float lo = bf16_lo(hv[u][e]), hi = bf16_hi(hv[u][e]);
+            ss += lo * lo; ss += hi * hi;
+        }
+        *reinterpret_cast<uint4*>(h + row + (size_t)c * 8) = make_uint4(hv[u][0], hv[u][1], hv[u][2], hv[u][3]);
+    }
+    if (!gain) return;
+    ss = wave_sum(ss);
+    if (lane == 0) wsum[wave] = ss;
+    __syncthreads();
+    const float total = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    const float rinv = 1.0f / sqrtf(total / (float)d + eps);
+#pragma unroll
+    for (int u = 0; u < NORM_MAX_CHUNKS; ++u) {
+        const int c = tid + u * 256;
+        if (c >= nch) continue;
+        const uint4 gq = *reinterpret_cast<const uint4*>(gain + (size_t)c * 8);
+        const uint32_t gw[4] = {gq.x, gq.y, gq.z, gq.w};
+        uint32_t o[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            o[e] = pack_bf16x2(bf16_lo(hv[u][e]) * rinv * bf16_lo(gw[e]), bf16_hi(hv[u][e]) * rinv * bf16_hi(gw[e]));
+        *reinterpret_cast<uint4*>(y + row + (size_t)c * 8) = make_uint4(o[0], o[1], o[2], o[3]);
+    }
+}
+
 // Rotary embedding, in place on q and k [rows, H, dh]: channel c < dh/2 of every head is paired with
 // channel c + dh/2 and the pair is turned by pos * theta^(-2c/dh).  The dh/2 angles of a token are the
 // same for all heads and for q and k: the first dh/2 threads evaluate them once, in double precision
@@ -96,6 +152,16 @@ int rmsnorm_run(const void* x, const void* gain, int rows, int d, float eps, voi
     if (d % 8 != 0 || d > 256 * NORM_MAX_CHUNKS * 8) return D3TOM_ERR_UNSUPPORTED;
     D3TOM_LAUNCH(RMSNORM, st, (rmsnorm_bf16_kernel<<<rows, 256, 0, st>>>((const uint16_t*)x, (const uint16_t*)gain, d, eps,
                                                                           (uint16_t*)y)));
+    return D3TOM_OK;
+}
+
+// h (may be the residual buffer itself) and, when gain is not null, y = rmsnorm(h)
+int add_norm_run(const float* part, int nsplit, const void* residual, const void* gain, int rows, int d, float eps,
+                 void* h, void* y, hipStream_t st) {
+    if (!part || !residual || !h || rows < 1 || d < 1 || nsplit < 1 || (gain && !y)) return D3TOM_ERR_INVALID_ARG;
+    if (d % 8 != 0 || d > 256 * NORM_MAX_CHUNKS * 8) return D3TOM_ERR_UNSUPPORTED;
+    D3TOM_LAUNCH(RMSNORM, st, (add_norm_bf16_kernel<<<rows, 256, 0, st>>>(part, nsplit, (size_t)rows * d, (const uint16_t*)residual,
+                                                                           (const uint16_t*)gain, d, eps, (uint16_t*)h, (uint16_t*)y)));
     return D3TOM_OK;
 }
 

@@ -5,6 +5,10 @@
 //   RESIDUAL  out = residual + a w^T                      (the block's two skip connections)
 //   SWIGLU    out = silu(a w_gate^T) * (a w_up^T)         (w holds the F gate rows, then the F up rows)
 // One rounding to bf16, at the store.
+//   PARTIAL   (inside the stack only) the contraction is cut into gridDim.y slices and every slice writes
+//             its float32 products to its own [rows, n] matrix; the row-wise kernel that follows adds the
+//             slices, the residual, rounds once and normalises.  Used where a short sequence leaves the
+//             output and down projections with too few tall tiles to fill the chip.
 //
 // Workgroup tile: (TM*64) rows x 128 columns of a w^T.  Eight waves with two jobs: waves 0..3 (2 x 2, wave
 // tile (TM*32) x 64) only feed the matrix cores, waves 4..7 only move data.  Both operands are
@@ -25,7 +29,7 @@
 
 namespace d3tom {
 
-enum { LIN_PLAIN = 0, LIN_RESIDUAL = 1, LIN_SWIGLU = 2 };
+enum { LIN_PLAIN = 0, LIN_RESIDUAL = 1, LIN_SWIGLU = 2, LIN_PARTIAL = 3 };
 constexpr int LIN_BN = 128;
 constexpr int LIN_BK = 64;
 constexpr int LIN_PAD = 136;      // floats per row of the epilogue staging tile (see the epilogue)
@@ -91,7 +95,8 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
         }
         b_off[i] = n * K * 2 + cg * 16;
     }
-    const int nkt = K / LIN_BK;
+    const int nkt = (K / LIN_BK) / (int)gridDim.y;         // k-stages of this workgroup's slice of the contraction
+    const int kt0 = (int)blockIdx.y * nkt;
     const uint32_t ring0 = (uint32_t)(size_t)(lds_ptr_t)ring;
     const uint32_t a_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (BM / 4) * 128);
     const uint32_t b_lds = __builtin_amdgcn_readfirstlane(ring0 + BM * 128 + wave * (LIN_BN / 4) * 128);
@@ -100,12 +105,12 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
         for (int i = 0; i < A_LD; ++i)
             if (i >= n0 && i < n1)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_a, (lds_ptr_t)(size_t)(a_lds + stage * STAGE + i * 8 * 128), 16,
-                                                         a_off[i], kt * (LIN_BK * 2), 0, 0);
+                                                         a_off[i], (kt0 + kt) * (LIN_BK * 2), 0, 0);
 #pragma unroll
         for (int i = 0; i < B_LD; ++i)
             if (A_LD + i >= n0 && A_LD + i < n1)
                 __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_w, (lds_ptr_t)(size_t)(b_lds + stage * STAGE + i * 8 * 128), 16,
-                                                         b_off[i], kt * (LIN_BK * 2), 0, 0);
+                                                         b_off[i], (kt0 + kt) * (LIN_BK * 2), 0, 0);
     };
 
     f32x16 acc[TM][2];
@@ -191,6 +196,12 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
         const float4 v0 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + cg * 8);
         const float4 v1 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + cg * 8 + 4);
         float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+        if constexpr (EPI == LIN_PARTIAL) {
+            float* po = reinterpret_cast<float*>(out) + ((size_t)blockIdx.y * M + m) * N + col;
+            *reinterpret_cast<float4*>(po) = v0;
+            *reinterpret_cast<float4*>(po + 4) = v1;
+            continue;
+        }
         const size_t o = (size_t)(col / out_chunk) * M * out_chunk + (size_t)m * out_chunk + col % out_chunk;
         if constexpr (EPI == LIN_SWIGLU) {
             const float4 u0 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + 64 + cg * 8);
@@ -216,7 +227,7 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
 namespace {
 template <int TM, int EPI>
 int launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out, int out_chunk,
-                  hipStream_t st) {
+                  int ksplit, hipStream_t st) {
     using C = LinCfg<TM>;
     static bool attr_done = false;       // per instantiation; the attribute only has to be set once per process
     if (!attr_done) {
@@ -233,7 +244,7 @@ int launch_linear(const void* a, const void* w, int M, int N, int K, const void*
     PC = PC < 4 ? 4 : (PC > 16 ? 16 : PC);
     if (PC > cpx) PC = cpx;
     const int panels = ceil_div(cpx, PC);
-    const unsigned grid = 8u * (unsigned)(panels * PC * NRT);
+    const dim3 grid(8u * (unsigned)(panels * PC * NRT), (unsigned)ksplit);
     D3TOM_LAUNCH(LINEAR, st, (linear_bf16_kernel<TM, EPI><<<grid, 512, C::LDS, st>>>(
         (const uint16_t*)a, (const uint16_t*)w, M, N, K, (const uint16_t*)residual, (uint16_t*)out, out_chunk,
         NRT, NCT, cpx, PC)));
@@ -244,9 +255,9 @@ template <int EPI>
 int launch_linear_tm(int tm, const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
                      int out_chunk, hipStream_t st) {
     switch (tm) {
-        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, st);
-        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, st);
-        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, st);
+        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, st);
+        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, st);
+        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, st);
     }
 }
 }  // namespace
@@ -269,6 +280,24 @@ int linear_pick_tm(int M, int n_tiles_n) {
         if (i == 0 || t < best_t - 1e-9) { best = tm; best_t = t; }
     }
     return best;
+}
+
+// Number of contraction slices for a projection whose result goes through the row-wise add-and-normalise
+// kernel anyway: 4 when the 256-row tiles of the whole problem fill at most a quarter of the chip and each
+// slice still has a long enough k-loop, else 1 (no split).
+int linear_split_plan(int M, int N, int K) {
+    const long tiles = (long)ceil_div(M, 256) * ceil_div(N, LIN_BN);
+    const int nkt = K / LIN_BK;
+    return (K % LIN_BK == 0 && N % 8 == 0 && tiles * 4 <= 256 && nkt % 4 == 0 && nkt >= 32) ? 4 : 1;
+}
+
+// a w^T as `ksplit` float32 partial matrices [ksplit][M][N] (256-row tiles)
+int linear_partial_run(const void* a, const void* w, int M, int N, int K, int ksplit, float* partial, hipStream_t st) {
+    if (!a || !w || !partial || M < 1 || N < 1 || K < 1 || ksplit < 1) return D3TOM_ERR_INVALID_ARG;
+    if (!aligned16(a) || !aligned16(w) || !aligned16(partial)) return D3TOM_ERR_INVALID_ARG;
+    if (K % (LIN_BK * ksplit) != 0 || N % 8 != 0) return D3TOM_ERR_UNSUPPORTED;
+    if ((size_t)M * K * 2 >= (1ull << 31) || (size_t)N * K * 2 >= (1ull << 31)) return D3TOM_ERR_UNSUPPORTED;
+    return launch_linear<4, LIN_PARTIAL>(a, w, M, N, K, nullptr, partial, N, ksplit, st);
 }
 
 int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, const void* residual, void* out,

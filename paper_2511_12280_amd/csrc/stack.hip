@@ -9,6 +9,13 @@ int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, 
                int out_chunk, int tm_override, hipStream_t st);
 int rmsnorm_run(const void* x, const void* gain, int rows, int d, float eps, void* y, hipStream_t st);
 int rope_run(void* q, void* k, const int32_t* pos, int rows, int H, int dh, float theta, hipStream_t st);
+int linear_split_plan(int M, int N, int K);
+int linear_partial_run(const void* a, const void* w, int M, int N, int K, int ksplit, float* partial, hipStream_t st);
+int add_norm_run(const float* part, int nsplit, const void* residual, const void* gain, int rows, int d, float eps,
+                 void* h, void* y, hipStream_t st);
+// float32 partial products of a split projection: the plan only splits while the 256 x 128 tiles of the result
+// number at most 64, i.e. at most 2 Mi elements per slice, 4 slices
+constexpr size_t STACK_PARTIAL_BYTES = (size_t)4 * 64 * 256 * 128 * sizeof(float);
 
 enum { LIN_PLAIN = 0, LIN_RESIDUAL = 1, LIN_SWIGLU = 2 };
 
@@ -46,7 +53,7 @@ __global__ void stack_copy_i32_kernel(const int32_t* __restrict__ src, int32_t* 
 }
 
 struct StackWs {
-    size_t meta, pos, h, hm, nrm, qkv, att, act, scores, kept, slot, assign, sub, sub_bytes, total;
+    size_t meta, pos, h, hm, nrm, qkv, att, act, part, scores, kept, slot, assign, sub, sub_bytes, total;
 };
 StackWs stack_ws_layout(int N, int d, int H, int F, int V, int max_D) {
     StackWs w;
@@ -59,6 +66,7 @@ StackWs stack_ws_layout(int N, int d, int H, int F, int V, int max_D) {
     w.qkv = take(3 * act_row);             // q, k, v of the current length, back to back
     w.att = take(act_row);
     w.act = take((size_t)N * F * 2);
+    w.part = take(STACK_PARTIAL_BYTES);
     w.scores = take((size_t)(V > 0 ? V : 1) * 4);
     w.kept = take((size_t)(V > 0 ? V : 1) * 4);
     w.slot = take((size_t)(V > 0 ? V : 1) * 4);
@@ -110,6 +118,7 @@ extern "C" int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L
     int32_t* pos = (int32_t*)(base + w.pos);
     void *h = base + w.h, *hm = base + w.hm, *nrm = base + w.nrm, *qkv = base + w.qkv;
     void *att = base + w.att, *act = base + w.act;
+    float* part = (float*)(base + w.part);
     float* scores = (float*)(base + w.scores);
     int32_t* kept = (int32_t*)(base + w.kept);
     int32_t* slot = (int32_t*)(base + w.slot);
@@ -126,10 +135,15 @@ extern "C" int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L
     int32_t* cu = meta + META_SEQ_OFF;
     int status;
 #define D3TOM_TRY(call) do { status = (call); if (status != D3TOM_OK) return status; } while (0)
+    // A projection whose result is short and narrow (output and down projection of the shortened sequence) is
+    // cut along the contraction; the row-wise kernel that adds its slices and the residual also writes the
+    // normalised rows the next sub-block starts from, so `nrm` may already be filled when a sub-block begins.
+    bool nrm_ready = false;
     for (int l = 1; l <= L; ++l) {
         const d3tom_block_weights& b = blocks[l - 1];
         const bool last = (l == L);
-        D3TOM_TRY(rmsnorm_run(cur, b.attn_norm, n, d, eps, nrm, st));
+        const bool merge_here = merging && l == merge_layer;
+        if (!nrm_ready) D3TOM_TRY(rmsnorm_run(cur, b.attn_norm, n, d, eps, nrm, st));
         // q | k | v in one projection, written as three [n, d] matrices back to back
         void* qq = qkv;
         void* kk = (char*)qkv + (size_t)n * d * 2;
@@ -140,9 +154,17 @@ extern "C" int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L
         // post-attention hidden state = residual + attention output projection; in place, except that the
         // caller's input is never written
         void* post = (cur == x) ? h : const_cast<void*>(cur);
-        D3TOM_TRY(linear_run(att, b.w_o, n, d, d, LIN_RESIDUAL, cur, post, 0, 0, st));
+        bool ffn_nrm_ready = false;
+        const int ks_o = linear_split_plan(n, d, d);
+        if (ks_o > 1) {
+            D3TOM_TRY(linear_partial_run(att, b.w_o, n, d, d, ks_o, part, st));
+            D3TOM_TRY(add_norm_run(part, ks_o, cur, merge_here ? nullptr : b.ffn_norm, n, d, eps, post, nrm, st));
+            ffn_nrm_ready = !merge_here;
+        } else {
+            D3TOM_TRY(linear_run(att, b.w_o, n, d, d, LIN_RESIDUAL, cur, post, 0, 0, st));
+        }
         void* ht = post;
-        if (merging && l == merge_layer) {
+        if (merge_here) {
             D3TOM_TRY(d3tom_importance(qq, kk, D3TOM_BF16, 1, meta + META_SEQ_OFF, H, dh, scale, dec_idx, meta + META_DEC_OFF,
                                        D, D, meta + META_VIS_START, meta + META_VIS_COUNT, meta + META_VIS_OFF, N, V,
                                        scores, sub, w.sub_bytes, st));
@@ -164,10 +186,18 @@ extern "C" int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L
             if (assign_out)
                 D3TOM_LAUNCH(STACK_META, st, (stack_copy_i32_kernel<<<ceil_div(V, 256), 256, 0, st>>>(asg, assign_out, V)));
         }
-        D3TOM_TRY(rmsnorm_run(ht, b.ffn_norm, n, d, eps, nrm, st));
+        if (!ffn_nrm_ready) D3TOM_TRY(rmsnorm_run(ht, b.ffn_norm, n, d, eps, nrm, st));
         D3TOM_TRY(linear_run(nrm, b.w_gate_up, n, 2 * F, d, LIN_SWIGLU, nullptr, act, 0, 0, st));
         void* outp = last ? y : ht;                  // in place, except that the last block writes the caller's y
-        D3TOM_TRY(linear_run(act, b.w_down, n, d, F, LIN_RESIDUAL, ht, outp, 0, 0, st));
+        const int ks_d = linear_split_plan(n, d, F);
+        if (ks_d > 1) {
+            D3TOM_TRY(linear_partial_run(act, b.w_down, n, d, F, ks_d, part, st));
+            D3TOM_TRY(add_norm_run(part, ks_d, ht, last ? nullptr : blocks[l].attn_norm, n, d, eps, outp, nrm, st));
+            nrm_ready = !last;
+        } else {
+            D3TOM_TRY(linear_run(act, b.w_down, n, d, F, LIN_RESIDUAL, ht, outp, 0, 0, st));
+            nrm_ready = false;
+        }
         cur = outp;
     }
 #undef D3TOM_TRY

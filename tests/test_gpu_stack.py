@@ -242,6 +242,7 @@ STACK_CASES = [
     (3, 512, 4, 704, 20, 729, 40, 9, 100, 1),          # one crop of visual tokens, head size 128, merge in block 1
     (3, 256, 2, 320, 7, 300, 21, 5, 299, 3),           # merge in the last block, one token merged away
     (2, 256, 4, 512, 0, 200, 8, 8, 1, 1),              # no prompt, everything merged into one token
+    (2, 2048, 16, 2048, 10, 120, 20, 6, 30, 1),        # wide enough that the output / down projections are split along k
 ]
 
 
