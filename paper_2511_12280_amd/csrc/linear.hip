@@ -44,7 +44,7 @@ template <int TM> struct LinCfg {
 template <int TM, int EPI>
 __global__ __launch_bounds__(512) void linear_bf16_kernel(
     const uint16_t* __restrict__ a, const uint16_t* __restrict__ w, int M, int N, int K,
-    const uint16_t* residual, uint16_t* out, int out_chunk, int NRT, int NCT, int cpx, int PC) {
+    const uint16_t* residual, uint16_t* out, int out_chunk, int NRT, int NCT, int cpx, int PC, int col0, int col_end) {
 #if defined(__HIP_DEVICE_COMPILE__)
     using C = LinCfg<TM>;
     constexpr int BM = C::BM, NS = C::NS, STAGE = C::STAGE;
@@ -87,11 +87,11 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
         const int cg = (lane & 7) ^ ((row >> 1) & 7);
         int n;
         if constexpr (EPI == LIN_SWIGLU) {
-            const int o = ct * 64 + (row & 63);
-            n = (o < n_out) ? o + (row >> 6) * n_out : 0;
+            const int o = col0 + ct * 64 + (row & 63);
+            n = (o < col_end) ? o + (row >> 6) * n_out : 0;
         } else {
-            n = ct * LIN_BN + row;
-            n = (n < N) ? n : 0;
+            n = col0 + ct * LIN_BN + row;
+            n = (n < col_end) ? n : 0;
         }
         b_off[i] = n * K * 2 + cg * 16;
     }
@@ -191,8 +191,8 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
     constexpr int CG = OUT_BN / 8;                         // 8-column groups per tile row
     for (int u = tid; u < BM * CG; u += NT) {
         const int row = u / CG, cg = u % CG;
-        const int m = rt * BM + row, col = ct * OUT_BN + cg * 8;
-        if (m >= M || col >= n_out) continue;
+        const int m = rt * BM + row, col = col0 + ct * OUT_BN + cg * 8;      // this launch covers columns [col0, col_end)
+        if (m >= M || col >= col_end) continue;
         const float4 v0 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + cg * 8);
         const float4 v1 = *reinterpret_cast<const float4*>(tile + row * LIN_PAD + cg * 8 + 4);
         float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
 namespace {
 template <int TM, int EPI>
 int launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out, int out_chunk,
-                  int ksplit, hipStream_t st) {
+                  int ksplit, int col0, int col_end, hipStream_t st) {
     using C = LinCfg<TM>;
     static bool attr_done = false;       // per instantiation; the attribute only has to be set once per process
     if (!attr_done) {
@@ -237,8 +237,7 @@ int launch_linear(const void* a, const void* w, int M, int N, int K, const void*
         attr_done = true;
     }
     const int out_bn = (EPI == LIN_SWIGLU) ? 64 : 128;
-    const int n_out = (EPI == LIN_SWIGLU) ? N / 2 : N;
-    const int NRT = ceil_div(M, C::BM), NCT = ceil_div(n_out, out_bn);
+    const int NRT = ceil_div(M, C::BM), NCT = ceil_div(col_end - col0, out_bn);
     const int cpx = ceil_div(NCT, 8);
     int PC = 32 / NRT;
     PC = PC < 4 ? 4 : (PC > 16 ? 16 : PC);
@@ -247,17 +246,17 @@ int launch_linear(const void* a, const void* w, int M, int N, int K, const void*
     const dim3 grid(8u * (unsigned)(panels * PC * NRT), (unsigned)ksplit);
     D3TOM_LAUNCH(LINEAR, st, (linear_bf16_kernel<TM, EPI><<<grid, 512, C::LDS, st>>>(
         (const uint16_t*)a, (const uint16_t*)w, M, N, K, (const uint16_t*)residual, (uint16_t*)out, out_chunk,
-        NRT, NCT, cpx, PC)));
+        NRT, NCT, cpx, PC, col0, col_end)));
     return D3TOM_OK;
 }
 
 template <int EPI>
 int launch_linear_tm(int tm, const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
-                     int out_chunk, hipStream_t st) {
+                     int out_chunk, int col0, int col_end, hipStream_t st) {
     switch (tm) {
-        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, st);
-        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, st);
-        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, st);
+        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st);
+        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st);
+        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st);
     }
 }
 }  // namespace
@@ -269,17 +268,38 @@ int launch_linear_tm(int tm, const void* a, const void* w, int M, int N, int K, 
 // But the grid runs in whole rounds of 256 workgroups (one per compute unit), so a partly filled last
 // round can cost more than the tile gains.  Estimated time = rounds * rows per tile / efficiency; the
 // smallest estimate wins, ties go to the smaller tile.
-int linear_pick_tm(int M, int n_tiles_n) {
-    const int cus = 256;
-    const double eff[3] = {0.55, 0.72, 1.0};
+static double linear_estimate(int tm, int M, int n_tiles_n) {
+    static const double eff[5] = {0.0, 0.55, 0.72, 0.0, 1.0};
+    const long tiles = (long)ceil_div(M, tm * 64) * n_tiles_n;
+    return (double)((tiles + 255) / 256) * tm / eff[tm];
+}
+int linear_pick_tm(int M, int n_tiles_n, double* est) {
     int best = 1;
     double best_t = 0.0;
-    for (int i = 0, tm = 1; i < 3; ++i, tm <<= 1) {
-        const long tiles = (long)ceil_div(M, tm * 64) * n_tiles_n;
-        const double t = (double)((tiles + cus - 1) / cus) * tm / eff[i];
-        if (i == 0 || t < best_t - 1e-9) { best = tm; best_t = t; }
+    for (int tm = 1; tm <= 4; tm <<= 1) {
+        const double t = linear_estimate(tm, M, n_tiles_n);
+        if (tm == 1 || t < best_t - 1e-9) { best = tm; best_t = t; }
     }
+    if (est) *est = best_t;
     return best;
+}
+// A last round that is mostly empty can be cut off: the leading column tiles that fill whole rounds of
+// 256-row tiles go in one launch, the remaining columns in a second launch with whatever tile suits them.
+// Returns the number of column tiles of the first launch (0 = one launch is as good) and both tile heights.
+int linear_plan_two(int M, int n_tiles_n, int* tm_a, int* tm_b) {
+    double single;
+    *tm_a = linear_pick_tm(M, n_tiles_n, &single);
+    *tm_b = 0;
+    const int nrt4 = ceil_div(M, 256);
+    const int rounds = (int)((long)nrt4 * n_tiles_n / 256);
+    if (rounds < 1) return 0;
+    const int cols_a = rounds * 256 / nrt4;
+    if (cols_a >= n_tiles_n) return 0;
+    double rest;
+    const int tb = linear_pick_tm(M, n_tiles_n - cols_a, &rest);
+    if (rounds * 4.0 + rest > 0.93 * single) return 0;         // not worth a second launch
+    *tm_a = 4; *tm_b = tb;
+    return cols_a;
 }
 
 // Number of contraction slices for a projection whose result goes through the row-wise add-and-normalise
@@ -297,7 +317,7 @@ int linear_partial_run(const void* a, const void* w, int M, int N, int K, int ks
     if (!aligned16(a) || !aligned16(w) || !aligned16(partial)) return D3TOM_ERR_INVALID_ARG;
     if (K % (LIN_BK * ksplit) != 0 || N % 8 != 0) return D3TOM_ERR_UNSUPPORTED;
     if ((size_t)M * K * 2 >= (1ull << 31) || (size_t)N * K * 2 >= (1ull << 31)) return D3TOM_ERR_UNSUPPORTED;
-    return launch_linear<4, LIN_PARTIAL>(a, w, M, N, K, nullptr, partial, N, ksplit, st);
+    return launch_linear<4, LIN_PARTIAL>(a, w, M, N, K, nullptr, partial, N, ksplit, 0, N, st);
 }
 
 int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, const void* residual, void* out,
@@ -316,13 +336,19 @@ int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, 
     // 32-bit byte offsets inside each operand
     if ((size_t)M * K * 2 >= (1ull << 31) || (size_t)N * K * 2 >= (1ull << 31)) return D3TOM_ERR_UNSUPPORTED;
     const int out_bn = (epilogue == LIN_SWIGLU) ? 64 : 128;
-    int tm = (tm_override == 1 || tm_override == 2 || tm_override == 4) ? tm_override
-                                                                        : linear_pick_tm(M, ceil_div(n_out, out_bn));
-    switch (epilogue) {
-        case LIN_PLAIN: return launch_linear_tm<LIN_PLAIN>(tm, a, w, M, N, K, residual, out, out_chunk, st);
-        case LIN_RESIDUAL: return launch_linear_tm<LIN_RESIDUAL>(tm, a, w, M, N, K, residual, out, out_chunk, st);
-        default: return launch_linear_tm<LIN_SWIGLU>(tm, a, w, M, N, K, residual, out, out_chunk, st);
-    }
+    auto launch = [&](int tm, int col0, int col_end) {
+        switch (epilogue) {
+            case LIN_PLAIN: return launch_linear_tm<LIN_PLAIN>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
+            case LIN_RESIDUAL: return launch_linear_tm<LIN_RESIDUAL>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
+            default: return launch_linear_tm<LIN_SWIGLU>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
+        }
+    };
+    if (tm_override == 1 || tm_override == 2 || tm_override == 4) return launch(tm_override, 0, n_out);
+    int tm_a, tm_b;
+    const int cols_a = linear_plan_two(M, ceil_div(n_out, out_bn), &tm_a, &tm_b);
+    if (cols_a == 0) return launch(tm_a, 0, n_out);
+    const int status = launch(tm_a, 0, cols_a * out_bn);
+    return status != D3TOM_OK ? status : launch(tm_b, cols_a * out_bn, n_out);
 }
 
 }  // namespace d3tom

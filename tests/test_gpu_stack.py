@@ -151,6 +151,30 @@ def test_linear_swiglu(B, M, F, K, tile):
     _one_step(_host(out), ref, f"swiglu {M}x{F}x{K} tile {tile}")
 
 
+def test_linear_two_launch_plan(B):
+    """Shapes whose 256-row tiles fill one round of the chip and a bit: the library cuts the columns into a
+    full round of tall tiles and a remainder with smaller tiles (two launches, one result)."""
+    rng = np.random.default_rng(21)
+    M, K, n = 300, 64, 22016
+    a = W.round_to(rng.standard_normal((M, K)).astype(np.float32), "bf16")
+    w = W.round_to((rng.standard_normal((n, K)) / np.sqrt(K)).astype(np.float32), "bf16")
+    r = W.round_to(rng.standard_normal((M, n)).astype(np.float32), "bf16")
+    ta, tw, tr = _dev(a), _dev(w), _dev(r)
+    out = torch.full((M, n), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(ta, tw, B.D3TOM_LINEAR_RESIDUAL, out, residual=tr)
+    torch.cuda.synchronize()
+    _one_step(_host(out), OS.round_bf16(r.astype(np.float64) + OS.linear(a, w)), "two-launch residual")
+    act = torch.full((M, n // 2), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(ta, tw, B.D3TOM_LINEAR_SWIGLU, act)
+    torch.cuda.synchronize()
+    _one_step(_host(act), OS.round_bf16(OS.swiglu(OS.linear(a, w[:n // 2]), OS.linear(a, w[n // 2:]))), "two-launch swiglu")
+    ch = torch.full((n // 128, M, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(ta, tw, B.D3TOM_LINEAR_PLAIN, ch, out_chunk=128)
+    torch.cuda.synchronize()
+    ref = OS.round_bf16(OS.linear(a, w))
+    _one_step(_host(ch).transpose(1, 0, 2).reshape(M, n), ref, "two-launch chunked")
+
+
 def test_linear_rejects(B):
     a = torch.zeros(4, 64, dtype=torch.bfloat16, device="cuda")
     w = torch.zeros(16, 64, dtype=torch.bfloat16, device="cuda")
