@@ -329,7 +329,7 @@ MEASURED_HBM_TRAFFIC = {
     "lavida_3645_sweep": {
         "imp_stats": 33.32e6, "imp_scores": 33.39e6, "imp_finish": 0.51e6, "topk_select": 0.05e6,
         "merge_norms": 9.07e6, "cos_argmax": 98.49e6, "merge_assign": 0.27e6, "merge_scatter": 41.33e6,
-        "attend": 40.20e6,
+        "attend": 40.98e6,
     },
 }
 
