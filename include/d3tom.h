@@ -318,7 +318,8 @@ size_t d3tom_stack_workspace_bytes(int N, int d, int H, int F, int V, int max_D)
  *   scores_out float[V], kept_idx_out int32[keep_k], assign_out int32[V]: the merge layer's intermediate
  *              results, out or NULL (written only when merging)
  *   n_out      HOST int out or NULL
- * dh must be 64 or 128, d and F multiples of 64.
+ * dh must be 64 or 128, d and F multiples of 64, d at most 8192, every activation and weight matrix below
+ * 2 GiB (otherwise D3TOM_ERR_UNSUPPORTED, before anything is enqueued).
  * ---------------------------------------------------------------------------------------- */
 int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L, const d3tom_block_weights* blocks /* host */,
                      int merge_layer, const int32_t* dec_idx, int D, int vis_start, int V, int keep_k, int mode,

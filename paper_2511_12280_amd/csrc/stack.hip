@@ -107,6 +107,11 @@ extern "C" int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L
     const int dh = d / H;
     if (dh != 64 && dh != 128) return D3TOM_ERR_UNSUPPORTED;
     if (d % 64 != 0 || F % 64 != 0) return D3TOM_ERR_UNSUPPORTED;
+    {   // every operand of a projection is addressed with 32-bit byte offsets: check here, before anything is enqueued
+        const size_t lim = (size_t)1 << 31, wide = (size_t)(d > F ? d : F);
+        if ((size_t)N * wide * 2 >= lim || (size_t)3 * d * d * 2 >= lim || (size_t)2 * F * d * 2 >= lim) return D3TOM_ERR_UNSUPPORTED;
+        if (d > 8192) return D3TOM_ERR_UNSUPPORTED;              // row-wise kernels keep a row in registers
+    }
     for (int l = 0; l < L; ++l) {
         const d3tom_block_weights& b = blocks[l];
         if (!b.attn_norm || !b.w_qkv || !b.w_o || !b.ffn_norm || !b.w_gate_up || !b.w_down) return D3TOM_ERR_INVALID_ARG;
