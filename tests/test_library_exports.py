@@ -64,6 +64,19 @@ def test_device_entry_points_reject_bad_arguments_without_a_gpu(lib):
     i = ctypes.c_int
     assert lib.d3tom_merge_kv(None, None, i(64), i(1), i(1), None, None, None, None, None, None, i(8), i(4), i(2), i(2), i(6),
                               i(0), None, None, None, None, None, None, None, ctypes.c_size_t(0), None) == 1
+    f = ctypes.c_float
+    for fn in ("d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_stack_step"):
+        getattr(lib, fn).restype = ctypes.c_int
+    assert lib.d3tom_rmsnorm(None, None, i(4), i(64), f(1e-5), None, None) == 1
+    assert lib.d3tom_rope(None, None, None, i(4), i(2), i(64), f(10000.0), None) == 1
+    assert lib.d3tom_linear(None, None, i(4), i(64), i(64), i(0), None, None, i(0), None) == 1
+    assert lib.d3tom_stack_step(None, i(8), i(256), i(4), i(512), i(1), None, i(1), None, i(0), i(0), i(4), i(2), i(0),
+                                f(1e-5), f(10000.0), None, None, None, None, None, None, None, ctypes.c_size_t(0), None) == 1
+    lib.d3tom_stack_workspace_bytes.restype = ctypes.c_size_t
+    small = lib.d3tom_stack_workspace_bytes(i(208), i(256), i(4), i(512), i(144), i(16))
+    big = lib.d3tom_stack_workspace_bytes(i(3773), i(4096), i(32), i(11008), i(3645), i(64))
+    assert 0 < small < big < (1 << 30)
+    assert lib.d3tom_stack_workspace_bytes(i(0), i(256), i(4), i(512), i(144), i(16)) == 0
 
 
 def test_schedule_variants_share_their_mean(lib):
