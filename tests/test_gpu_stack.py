@@ -472,3 +472,51 @@ def test_stack_full_size_two_blocks_against_oracle(B):
           f"kept diff {len(diff) // 2}, assign diff {len(wrong)}")
     # floor of bf16 storage measured by the oracle on itself at small sizes: 5e-3 .. 7e-3 for 2 .. 4 blocks
     assert rel < 2e-2, rel
+
+
+def test_stack_trajectory_with_decider_updates(B):
+    """Three denoising steps of a small stack the way the benchmark drives the full one: decider set from two
+    successive token-id states on the device, embedding of the current response tokens, one stack step.
+    Step 0 has no deciders and runs unmerged (Algorithm 1); later steps merge."""
+    L, d, H, F, Pn, V, O, keep_k = 2, 256, 4, 512, 6, 80, 10, 20
+    case = W.stack_case(91, L=L, d=d, H=H, F=F, P=Pn, V=V, O=O, D=0, std=1.0 / 16, gain_jitter=0.1)
+    N = case["N"]
+    mask_id = 126336
+    states = W.mask_trajectory(5, Pn + V, O, 3, mask_id)
+    rng = np.random.default_rng(17)
+    table = W.round_to(rng.standard_normal((64, d)).astype(np.float32), "bf16")
+    mask_vec = W.round_to(rng.standard_normal(d).astype(np.float32), "bf16")
+    gb = _gpu_blocks(case)
+    arr = B.block_weights(gb)
+    ws = B.workspace(B.d3tom_stack_workspace_bytes(N, d, H, F, V, 16))
+    seq_off = torch.tensor([0, N], dtype=torch.int32, device="cuda")
+    dec_idx = torch.zeros(16, dtype=torch.int32, device="cuda")
+    dec_off = torch.zeros(2, dtype=torch.int32, device="cuda")
+    dec_count = torch.zeros(1, dtype=torch.int32, device="cuda")
+    merged_steps = 0
+    for s in range(3):
+        x = case["x"].copy()
+        ids = states[s][Pn + V:]
+        x[Pn + V:] = np.where((ids == mask_id)[:, None], mask_vec[None, :], table[ids % 64])
+        D = 0
+        dec_ref = np.zeros(0, np.int32)
+        if s > 0:
+            B.d3tom_update_deciders(torch.from_numpy(states[s - 1]).cuda(), torch.from_numpy(states[s]).cuda(), mask_id, seq_off,
+                                    16, dec_idx, dec_off, dec_count)
+            D = int(dec_count.item())
+            dec_ref = oracle.deciders(states[s - 1], states[s], mask_id)
+            np.testing.assert_array_equal(dec_idx[:D].cpu().numpy(), dec_ref)
+        y = torch.zeros(N, d, dtype=torch.bfloat16, device="cuda")
+        kept = torch.zeros(keep_k, dtype=torch.int32, device="cuda")
+        asg = torch.zeros(V, dtype=torch.int32, device="cuda")
+        n_out = B.d3tom_stack_step(_dev(x), H, F, arr, L, 1, dec_idx if D else None, D, Pn, V, keep_k, 0, 1e-5, 10000.0, y, ws,
+                                   kept_idx=kept, assign=asg)
+        torch.cuda.synchronize()
+        over = dict(kept_override=kept.cpu().numpy(), assign_override=asg.cpu().numpy()) if D else {}
+        ref = OS.stack_step(x, _oracle_blocks(case), H, dec_ref if D else None, Pn, V, keep_k, 1, **over)
+        assert n_out == ref["y"].shape[0] == (N - (V - keep_k) if D else N)
+        merged_steps += int(D > 0)
+        got = _host(y[:n_out])
+        rel = np.sqrt(np.mean((got - ref["y"]) ** 2)) / np.sqrt(np.mean(ref["y"] ** 2))
+        assert rel < 2e-2, (s, rel)          # 3x the rounding floor measured for two to four blocks
+    assert merged_steps == 2
