@@ -218,6 +218,33 @@ def run_kv_cache(wl_name: str, steps: int, warmup: int):
                 kernels={k: round(ms * 1e3 / c, 3) for k, (ms, c) in prof.items() if c})
 
 
+def time_attention(wl_name: str, n_tokens: int, steps: int, warmup: int) -> float:
+    """d3tom_attend alone on sequences of n_tokens of the workload's shape (several input sets, so K / V come
+    from HBM as in the step); microseconds per call."""
+    from paper_2511_12280_amd import binding as B
+    from paper_2511_12280_amd import workloads as W
+    wl = W.WORKLOADS[wl_name]
+    g = W.SampleGen(wl)
+    sets = [tuple(B.to_device(a, wl.dtype) for a in g.attention_inputs(n_tokens, 32)) for _ in range(8)]
+    tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
+    o = torch.zeros((n_tokens, wl.H, wl.dh), dtype=tdt, device="cuda")
+    cu = torch.tensor([0, n_tokens], dtype=torch.int32, device="cuda")
+    scale = 1.0 / float(np.sqrt(wl.dh))
+    def step(i):
+        q, k, v = sets[i % len(sets)]
+        B.d3tom_attend(q, k, v, cu, n_tokens, scale, o)
+    # calls of ~10 us: a long warm-up, or the clocks are still ramping after the host-side input generation
+    warmup, steps = max(warmup, 1000), max(steps, 500)
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e6 / steps
+
+
 def run_stack(traj_repeats: int = 1):
     """Whole denoising trajectory through the 32-block stack (the full-stack configuration): T steps, each
     = decider update on the device, embedding of the current response tokens (a row gather, plumbing),
@@ -385,6 +412,10 @@ def main():
         line["also"] = {args.also: {"steps_per_s": round(r2["steps_per_s"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
                                     "merge_layer_us": r2["merge_layer_us"], "attend_us": r2["attend_us"],
                                     "kernels": r2["kernels"]}}
+        if args.also == "llada_v_1024":
+            # the workload text quotes 263 tokens after the merge, its own counts give 231 (timed above): both lengths
+            line["also"][args.also]["attend_alone_us"] = {str(n): round(time_attention(args.also, n, args.steps, args.warmup), 2)
+                                                          for n in (231, 263)}
         line["also"]["kv_cache_of_" + args.workload] = run_kv_cache(args.workload, args.steps, args.warmup)
         if not args.no_stack:
             line["also"]["denoise_stack_3645"] = run_stack()
