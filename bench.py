@@ -247,7 +247,7 @@ def time_attention(wl_name: str, n_tokens: int, steps: int, warmup: int) -> floa
 
 def run_stack(traj_repeats: int = 1):
     """Whole denoising trajectory through the 32-block stack (the full-stack configuration): T steps, each
-    = decider update on the device, embedding of the current response tokens (a row gather, plumbing),
+    = decider update on the device, embedding of the current response tokens (one row gather, plumbing),
     d3tom_stack_step.  Step 0 has no deciders and runs unmerged; every later step merges inside block l*.
     Which response positions are revealed when comes from the synthetic scheduler (no decoding head)."""
     from paper_2511_12280_amd import binding as B
@@ -266,7 +266,12 @@ def run_stack(traj_repeats: int = 1):
     ws = B.workspace(B.d3tom_stack_workspace_bytes(N, d, H, F, V, B.D3TOM_MAX_DECIDERS))
     x = inp["x"].clone()
     y = torch.zeros(N, d, dtype=torch.bfloat16, device="cuda")
-    resp = slice(P + V, N)
+    # embedding rows of the response positions: one table with the [MASK] row appended, and per state the row
+    # index of every response position (the scheduler's output in the form the gather takes)
+    table = torch.cat([inp["table"], inp["mask_vec"][None, :]], dim=0)
+    resp_ids = states[:, P + V:].long()
+    emb_idx = torch.where(resp_ids == cfg["mask_id"], torch.full_like(resp_ids, cfg["table_rows"]), resp_ids % cfg["table_rows"])
+    x_resp = x[P + V:]                                     # view of the response rows of x
 
     def step(s: int) -> int:
         cur = states[s]
@@ -274,8 +279,7 @@ def run_stack(traj_repeats: int = 1):
         if s > 0:
             B.d3tom_update_deciders(states[s - 1], cur, cfg["mask_id"], seq_off, B.D3TOM_MAX_DECIDERS, dec_idx, dec_off, dec_count)
             D = min(int(dec_count.item()), B.D3TOM_MAX_DECIDERS)       # 4 bytes back to the host: the launch sizes need it
-        ids = cur[resp].long()
-        x[resp] = torch.where((ids == cfg["mask_id"])[:, None], inp["mask_vec"][None, :], inp["table"][ids % cfg["table_rows"]])
+        torch.index_select(table, 0, emb_idx[s], out=x_resp)
         return B.d3tom_stack_step(x, H, F, arr, L, cfg["merge_layer"], dec_idx, D, P, V, keep_k, B.D3TOM_MERGE_MEAN,
                                   cfg["eps"], cfg["theta"], y, ws)
 
