@@ -123,6 +123,26 @@ def test_topk_exact_including_ties_and_extremes():
         np.testing.assert_array_equal(sg, sr)
 
 
+# ---- workspace -------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("P,V,O,D,k,d", [(8, 700, 16, 9, 150, 512),      # normal cosine path (several tiles)
+                                          (4, 300, 8, 5, 40, 4096)])      # few tiles, long rows: split along k
+def test_workspace_contents_do_not_matter(P, V, O, D, k, d):
+    """The workspace carries no state: whatever bytes it holds on entry (zeros, all-ones = NaN / -1), the
+    outputs are bit-identical."""
+    c = W.random_case(11, P + V + O, d, d // 128, P, V, D, dtype="bf16", centres=30)
+    runs = []
+    for fill in (0, 255):
+        step = GpuStep([c], [k], "bf16")
+        step.ws_imp.fill_(fill); step.ws_merge.fill_(fill)
+        S = step.importance()
+        step.ws_imp.fill_(fill)
+        kept, slot = step.select_topk()
+        mout = step.merge()
+        runs.append((S[0], kept[0], mout["y"][0], mout["assign"][0], mout["counts"][0], mout["src_pos"][0]))
+    for a, b in zip(*runs):
+        np.testing.assert_array_equal(a, b)
+
+
 # ---- attention in isolation ---------------------------------------------------------------------------
 @pytest.mark.parametrize("H,dh,dtype", [(4, 128, "bf16"), (3, 64, "bf16"), (2, 64, "f32"), (2, 40, "bf16")])
 def test_attend_varlen(H, dh, dtype):

@@ -520,3 +520,21 @@ def test_stack_trajectory_with_decider_updates(B):
         rel = np.sqrt(np.mean((got - ref["y"]) ** 2)) / np.sqrt(np.mean(ref["y"] ** 2))
         assert rel < 2e-2, (s, rel)          # 3x the rounding floor measured for two to four blocks
     assert merged_steps == 2
+
+
+def test_stack_workspace_contents_do_not_matter(B):
+    case = W.stack_case(93, L=2, d=2048, H=16, F=2048, P=6, V=90, O=8, D=4, std=1.0 / 45, gain_jitter=0.1)
+    N, d, H, F, V = case["N"], 2048, 16, 2048, 90
+    gbs = _gpu_blocks(case)            # the pointer table below refers to these tensors: keep them alive
+    arr = B.block_weights(gbs)
+    x = _dev(case["x"])
+    dec = torch.from_numpy(case["dec_idx"]).cuda()
+    outs = []
+    for fill in (0, 255):
+        ws = B.workspace(B.d3tom_stack_workspace_bytes(N, d, H, F, V, 4))
+        ws.fill_(fill)
+        y = torch.zeros(N, d, dtype=torch.bfloat16, device="cuda")
+        n_out = B.d3tom_stack_step(x, H, F, arr, 2, 1, dec, 4, case["vis_start"], V, 25, 0, 1e-5, 10000.0, y, ws)
+        torch.cuda.synchronize()
+        outs.append(y[:n_out].clone())
+    assert torch.equal(outs[0], outs[1])
