@@ -729,8 +729,9 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
     const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0) && ((size_t)max_V * d_sim * 2 < ((size_t)1 << 31));
     if (mfma) {
         const int nct = ceil_div(max_keep, COS_BN);
-        // 128-row tiles unless that leaves most of the 256 CUs idle
-        const int TM = ((long)nct * ceil_div(max_pruned, 128) * B >= 96) ? 2 : 1;
+        // as long as the 64-row tiles still fit one round of the 256 CUs they finish sooner than half as many
+        // 128-row tiles (a 64-row tile's k-loop is ~0.7 of a 128-row tile's)
+        const int TM = ((long)nct * ceil_div(max_pruned, 64) * B > 256) ? 2 : 1;
         // too few 64 x 128 tiles for 256 CUs (short sequences): cut the contraction into k-slices as well
         int ksplit = 1;
         if (TM == 1) {
