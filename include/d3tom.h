@@ -122,6 +122,28 @@ int d3tom_importance(const void* q, const void* k, int dt,
                      float* scores, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * d3tom_importance_static — d3tom_importance for callers that cannot allocate device memory: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical scores, but no workspace argument: the scratch memory is a
+ * file-scope device array of D3TOM_IMPORTANCE_STATIC_BYTES inside the library, which every GPU the
+ * library runs on holds until the process ends.  The call allocates and frees nothing (no
+ * hipMalloc / hipFree, no allocating library routine); the first call on a device only looks up
+ * the array's device address.
+ *
+ * Shapes whose workspace (d3tom_workspace_bytes(D3TOM_OP_IMPORTANCE, ...)) exceeds
+ * D3TOM_IMPORTANCE_STATIC_BYTES return D3TOM_ERR_UNSUPPORTED before anything is enqueued.  All calls
+ * on one GPU share that GPU's array, which keeps the previous call's contents (no kernel relies on
+ * them): two calls that overlap on one GPU (different streams or threads) race and give
+ * unspecified scores; calls on one stream are ordered and safe.
+ * ---------------------------------------------------------------------------------------- */
+#define D3TOM_IMPORTANCE_STATIC_BYTES (16u << 20)
+int d3tom_importance_static(const void* q, const void* k, int dt,
+                            int B, const int32_t* seq_off, int H, int dh, float scale,
+                            const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                            const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                            int max_N, int max_V, float* scores, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * d3tom_select_topk — keep / merge partition (Section 3.2: V_kept holds the tokens whose rank is
  * at most the kept count; Algorithm 1, the TopK line).
  *

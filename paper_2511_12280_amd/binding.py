@@ -28,10 +28,11 @@ D3TOM_F32, D3TOM_BF16 = 0, 1
 D3TOM_MERGE_MEAN, D3TOM_MERGE_SUM = 0, 1
 D3TOM_OP_IMPORTANCE, D3TOM_OP_SELECT_TOPK, D3TOM_OP_MERGE, D3TOM_OP_ATTEND = range(4)
 D3TOM_MAX_VISUAL, D3TOM_MAX_DECIDERS = 16384, 256
+D3TOM_IMPORTANCE_STATIC_BYTES = 16 << 20
 D3TOM_LINEAR_PLAIN, D3TOM_LINEAR_RESIDUAL, D3TOM_LINEAR_SWIGLU = range(3)
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
-           "d3tom_status_string", "d3tom_importance", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_update_deciders",
+           "d3tom_status_string", "d3tom_importance", "d3tom_importance_static", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_update_deciders",
            "d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_linear_tile", "d3tom_stack_workspace_bytes", "d3tom_stack_step",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
@@ -49,6 +50,8 @@ _lib.d3tom_status_string.argtypes = [_i]
 _lib.d3tom_importance.restype = _i
 _lib.d3tom_importance.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _f, _vp, _vp, _i, _i, _vp, _vp, _vp, _i, _i,
                                   _vp, _vp, _sz, _vp]
+_lib.d3tom_importance_static.restype = _i
+_lib.d3tom_importance_static.argtypes = [_vp, _vp, _i, _i, _vp, _i, _i, _f, _vp, _vp, _i, _i, _vp, _vp, _vp, _i, _i, _vp, _vp]
 _lib.d3tom_select_topk.restype = _i
 _lib.d3tom_select_topk.argtypes = [_vp, _i, _vp, _vp, _vp, _i, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_merge.restype = _i
@@ -218,6 +221,17 @@ def d3tom_importance(q: torch.Tensor, k: torch.Tensor, lay: Layout, scale: float
                                  _ptr(lay.dec_idx), _ptr(lay.dec_off), lay.min_D, lay.max_D,
                                  _ptr(lay.vis_start), _ptr(lay.vis_count), _ptr(lay.vis_off), lay.max_N, lay.max_V,
                                  _ptr(scores), _ptr(ws), ws.numel(), _stream(stream)), "d3tom_importance")
+    return scores
+
+
+def d3tom_importance_static(q: torch.Tensor, k: torch.Tensor, lay: Layout, scale: float,
+                            scores: torch.Tensor, stream=None) -> torch.Tensor:
+    """d3tom_importance without a workspace argument (the library's own static scratch array)."""
+    H, dh = q.shape[-2], q.shape[-1]
+    _check(_lib.d3tom_importance_static(_ptr(q), _ptr(k), _dt(q), lay.B, _ptr(lay.seq_off), H, dh, float(scale),
+                                        _ptr(lay.dec_idx), _ptr(lay.dec_off), lay.min_D, lay.max_D,
+                                        _ptr(lay.vis_start), _ptr(lay.vis_count), _ptr(lay.vis_off), lay.max_N, lay.max_V,
+                                        _ptr(scores), _stream(stream)), "d3tom_importance_static")
     return scores
 
 

@@ -18,6 +18,7 @@
 // becomes a comparable share of the run time.
 //
 // The generic path (any float type / head size) is a plain one-thread-per-output kernel pair.
+#include <mutex>
 #include "common.hpp"
 
 namespace d3tom {
@@ -330,12 +331,11 @@ __global__ __launch_bounds__(256) void imp_scores_generic(
 
 using namespace d3tom;
 
-extern "C" int d3tom_importance(const void* q, const void* k, int dt,
-                                int B, const int32_t* seq_off, int H, int dh, float scale,
-                                const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
-                                const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
-                                int max_N, int max_V,
-                                float* scores, void* ws, size_t ws_bytes, void* stream) {
+// Host-side argument checks shared by the two entry points (everything except the workspace).
+static int importance_check(const void* q, const void* k, int dt, int B, const int32_t* seq_off, int H, int dh, float scale,
+                            const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                            const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                            int max_N, int max_V, const float* scores) {
     if (!q || !k || !seq_off || !dec_idx || !dec_off || !vis_start || !vis_count || !score_off || !scores)
         return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || H < 1 || dh < 1 || max_N < 1 || max_V < 1 || max_V > max_N || min_D < 0 || max_D < min_D)
@@ -346,8 +346,16 @@ extern "C" int d3tom_importance(const void* q, const void* k, int dt,
     if (min_D == 0) return D3TOM_ERR_NO_DECIDERS;
     if (max_D > D3TOM_MAX_DECIDERS) return D3TOM_ERR_UNSUPPORTED;
     if (dh > 256 || (dt == D3TOM_BF16 ? (dh % 8) : (dh % 4))) return D3TOM_ERR_UNSUPPORTED;
+    return D3TOM_OK;
+}
+
+// The launches; arguments and workspace have been checked.
+static int importance_run(const void* q, const void* k, int dt,
+                          int B, const int32_t* seq_off, int H, int dh, float scale,
+                          const int32_t* dec_idx, const int32_t* dec_off, int max_D,
+                          const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                          int max_N, int max_V, float* scores, void* ws, void* stream) {
     const ImpWs w = imp_ws_layout(B, max_N, max_V, H, max_D);
-    if (!ws || ws_bytes < w.total || (((uintptr_t)ws) & 255u)) return ws ? D3TOM_ERR_WORKSPACE_TOO_SMALL : D3TOM_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     char* wsb = (char*)ws;
     const float scale2 = scale * LOG2E;
@@ -391,4 +399,57 @@ extern "C" int d3tom_importance(const void* q, const void* k, int dt,
             score_off, max_D, max_V, cws, scores));
     }
     return D3TOM_OK;
+}
+
+extern "C" int d3tom_importance(const void* q, const void* k, int dt,
+                                int B, const int32_t* seq_off, int H, int dh, float scale,
+                                const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                                const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                                int max_N, int max_V,
+                                float* scores, void* ws, size_t ws_bytes, void* stream) {
+    const int rc = importance_check(q, k, dt, B, seq_off, H, dh, scale, dec_idx, dec_off, min_D, max_D, vis_start,
+                                    vis_count, score_off, max_N, max_V, scores);
+    if (rc != D3TOM_OK) return rc;
+    const ImpWs w = imp_ws_layout(B, max_N, max_V, H, max_D);
+    if (!ws || ws_bytes < w.total || (((uintptr_t)ws) & 255u)) return ws ? D3TOM_ERR_WORKSPACE_TOO_SMALL : D3TOM_ERR_INVALID_ARG;
+    return importance_run(q, k, dt, B, seq_off, H, dh, scale, dec_idx, dec_off, max_D, vis_start, vis_count, score_off,
+                          max_N, max_V, scores, ws, stream);
+}
+
+// ---- the same call for callers that cannot allocate ---------------------------------------------
+// The workspace is a file-scope device array instead of a caller buffer.  Every GPU the library runs on
+// holds its own copy of the array at its own address; host code never uses the array's name as an
+// address (it is a host-side stand-in) but the device address of the current GPU's copy, asked for
+// once per device and kept.
+static __device__ __align__(256) unsigned char scratch[D3TOM_IMPORTANCE_STATIC_BYTES];
+
+namespace {
+constexpr int MAX_GPUS = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[MAX_GPUS] = {};
+}
+
+extern "C" int d3tom_importance_static(const void* q, const void* k, int dt,
+                                       int B, const int32_t* seq_off, int H, int dh, float scale,
+                                       const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                                       const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
+                                       int max_N, int max_V, float* scores, void* stream) {
+    const int rc = importance_check(q, k, dt, B, seq_off, H, dh, scale, dec_idx, dec_off, min_D, max_D, vis_start,
+                                    vis_count, score_off, max_N, max_V, scores);
+    if (rc != D3TOM_OK) return rc;
+    if (imp_ws_layout(B, max_N, max_V, H, max_D).total > (size_t)D3TOM_IMPORTANCE_STATIC_BYTES) return D3TOM_ERR_UNSUPPORTED;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_GPUS) return D3TOM_ERR_DEVICE;
+    void* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lk(g_scratch_mu);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return D3TOM_ERR_DEVICE;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    return importance_run(q, k, dt, B, seq_off, H, dh, scale, dec_idx, dec_off, max_D, vis_start, vis_count, score_off,
+                          max_N, max_V, scores, ptr, stream);
 }
