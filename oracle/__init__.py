@@ -57,7 +57,7 @@ def lib():
         L.oracle_merge.argtypes = [_f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, _i32p,
                                    ctypes.c_int, _i32p, ctypes.c_int, _f64p, _i32p, _i32p]
         L.oracle_attend.argtypes = [_f32p, _f32p, _f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
-                                    ctypes.c_double, _f64p, _i32p, ctypes.c_int]
+                                    ctypes.c_double, _f64p, _f64p, _i32p, ctypes.c_int]
         for name, n in (("oracle_flops_layer", 3), ("oracle_flops_attn", 2), ("oracle_flops_ffn", 3),
                         ("oracle_flops_merge", 3)):
             f = getattr(L, name)
@@ -171,15 +171,19 @@ def merge(x, vis_start: int, V: int, kept_idx, assign_, mode: str = "mean"):
     return y, counts, src
 
 
-def attend(q, k, v, scale: Optional[float] = None, rows=None) -> np.ndarray:
-    """out [n, H, dh] float64, no mask.  `rows`: optional query rows to evaluate (others stay 0)."""
+def attend(q, k, v, scale: Optional[float] = None, rows=None, key_weight=None) -> np.ndarray:
+    """out [n, H, dh] float64, no mask.  `rows`: optional query rows to evaluate (others stay 0);
+    `key_weight` [n]: optional positive per-key weights (softmax of logit + log weight)."""
     q = _f32(q); k = _f32(k); v = _f32(v)
     n, H, dh = q.shape
     assert k.shape == q.shape and v.shape == q.shape
     scale = 1.0 / np.sqrt(dh) if scale is None else scale
     out = np.zeros((n, H, dh), dtype=np.float64)
     r = _i32(rows) if rows is not None else None
-    _check(lib().oracle_attend(_p(q, _f32p), _p(k, _f32p), _p(v, _f32p), n, H, dh, float(scale), _p(out, _f64p),
+    w = np.ascontiguousarray(key_weight, dtype=np.float64) if key_weight is not None else None
+    assert w is None or w.shape == (n,)
+    _check(lib().oracle_attend(_p(q, _f32p), _p(k, _f32p), _p(v, _f32p), n, H, dh, float(scale),
+                               _p(w, _f64p) if w is not None else None, _p(out, _f64p),
                                _p(r, _i32p) if r is not None else None, len(r) if r is not None else 0), "attend")
     return out
 

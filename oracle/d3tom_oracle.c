@@ -263,14 +263,25 @@ int oracle_merge(const float* x, int N, int d, int vis_start, int V,
  * 2 n^2 d term of the per-layer cost; no causal mask, every query sees every
  * key).  Per head: O = softmax(scale * Q K^T) V.
  *
- *   q, k, v [n, H, dh]   out [n, H, dh]
- *   rows    [n_rows] optional: query rows to evaluate (NULL = all n); other rows of out are left alone
+ * Size-weighted form (reading M1).  Under MEAN aggregation a merged row stands
+ * for count_r original tokens but enters the softmax of the later layers once,
+ * so the attention mass those tokens had is lost; SUM aggregation (the paper's
+ * literal update) keeps it in the row's magnitude instead.  With per-key weights
+ * w_j (the member counts the merge reports) the attention probabilities become
+ * p_ij = w_j exp(l_ij) / sum_j' w_j' exp(l_ij'), i.e. softmax(l_ij + log w_j):
+ * exactly what attention over the sequence with key/value row j written w_j
+ * times would give.  key_weight == NULL is the plain form (all w_j = 1).
+ *
+ *   q, k, v     [n, H, dh]   out [n, H, dh]
+ *   key_weight  [n] optional, every entry > 0
+ *   rows        [n_rows] optional: query rows to evaluate (NULL = all n); other rows of out are left alone
  */
 int oracle_attend(const float* q, const float* k, const float* v, int n, int H, int dh, double scale,
-                  double* out, const int32_t* rows, int n_rows) {
+                  const double* key_weight, double* out, const int32_t* rows, int n_rows) {
     if (n <= 0 || H <= 0 || dh <= 0) return 1;
     if (!rows) n_rows = n;
     for (int t = 0; rows && t < n_rows; ++t) if (rows[t] < 0 || rows[t] >= n) return 1;
+    for (int j = 0; key_weight && j < n; ++j) if (!(key_weight[j] > 0.0)) return 1;
 #pragma omp parallel for collapse(2) schedule(dynamic, 16)
     for (int h = 0; h < H; ++h) {
         for (int t = 0; t < n_rows; ++t) {
@@ -286,7 +297,11 @@ int oracle_attend(const float* q, const float* k, const float* v, int n, int H, 
                 if (p[j] > mx) mx = p[j];
             }
             double z = 0.0;
-            for (int j = 0; j < n; ++j) { p[j] = exp(p[j] - mx); z += p[j]; }
+            for (int j = 0; j < n; ++j) {
+                p[j] = exp(p[j] - mx);
+                if (key_weight) p[j] *= key_weight[j];
+                z += p[j];
+            }
             double* o = out + ((size_t)i * H + h) * dh;
             for (int c = 0; c < dh; ++c) o[c] = 0.0;
             for (int j = 0; j < n; ++j) {

@@ -40,15 +40,16 @@ def round_bf16(a) -> np.ndarray:
     return np.ldexp(np.rint(m * 256.0), e - 8)   # rint: ties to even
 
 
-def _store_fn(store, jitter: float = 0.0, seed: int = 0) -> Callable[[np.ndarray], np.ndarray]:
+def _store_fn(store) -> Callable[[np.ndarray], np.ndarray]:
+    """The function applied to every tensor at a hand-over point: identity in float64 (None), rounding to
+    bf16 ("bf16"), or a caller's own function of one array."""
     if store is None:
         return lambda a: np.asarray(a, dtype=np.float64)
     if store == "bf16":
-        if jitter == 0.0:
-            return round_bf16
-        rng = np.random.default_rng(seed)
-        return lambda a: round_bf16(np.asarray(a, dtype=np.float64) * (1.0 + jitter * rng.standard_normal(np.shape(a))))
-    raise ValueError("store must be None or 'bf16'")
+        return round_bf16
+    if callable(store):
+        return store
+    raise ValueError("store must be None, 'bf16' or a function")
 
 
 def rmsnorm(x, gain, eps: float) -> np.ndarray:
@@ -104,65 +105,61 @@ class Block:
         self.ffn_norm, self.w_gate, self.w_up, self.w_down = ffn_norm, w_gate, w_up, w_down
 
 
+def attention_part(h, blk: Block, H: int, pos, eps: float, theta: float, rt) -> tuple:
+    """First half of a block on hidden states h [n, d] whose tokens sit at positions pos [n]:
+        a = rmsnorm(h);  q, k, v = a Wq^T, a Wk^T, a Wv^T;  q, k rotated at pos;
+        h~ = h + attention(q, k, v) Wo^T
+    rt is applied to every tensor where it is handed on.  Returns (h~, rotated q, rotated k)."""
+    n, d = h.shape
+    dh = d // H
+    a = rt(rmsnorm(h, blk.attn_norm, eps))
+    q = rt(linear(a, blk.wq)).reshape(n, H, dh)
+    k = rt(linear(a, blk.wk)).reshape(n, H, dh)
+    v = rt(linear(a, blk.wv)).reshape(n, H, dh)
+    q = rt(rope(q, pos, theta)); k = rt(rope(k, pos, theta))
+    o = rt(attention(q, k, v)).reshape(n, d)
+    return rt(h + linear(o, blk.wo)), q, k
+
+
+def ffn_part(ht, blk: Block, eps: float, rt) -> np.ndarray:
+    """Second half of a block: h = h~ + (silu(f Wg^T) * (f Wu^T)) Wd^T with f = rmsnorm(h~)."""
+    f = rt(rmsnorm(ht, blk.ffn_norm, eps))
+    act = rt(swiglu(linear(f, blk.w_gate), linear(f, blk.w_up)))
+    return rt(ht + linear(act, blk.w_down))
+
+
 def stack_step(x, blocks: Sequence[Block], H: int, dec_idx, vis_start: int, V: int, keep_k: int,
-               merge_layer: int, eps: float = 1e-5, theta: float = 10000.0, store="bf16",
-               kept_override=None, assign_override=None, mode: str = "mean", jitter: float = 0.0,
-               jitter_seed: int = 0) -> dict:
+               merge_layer: int, eps: float = 1e-5, theta: float = 10000.0, store="bf16", mode: str = "mean") -> dict:
     """One denoising step: hidden states x [N, d] through all blocks.
 
     Per block l = 1 .. L (pre-norm residual blocks):
-        a = rmsnorm(h);  q, k, v = a Wq^T, a Wk^T, a Wv^T;  q, k rotated at the tokens' positions;
-        h~ = h + attention(q, k, v) Wo^T                       (post-attention hidden state)
+        h~, q, k = attention_part(h)                           (post-attention hidden state)
         if l == merge_layer and there are deciders:            (Algorithm 1)
             S from this block's q, k (the attention it just used);  keep the keep_k best visual tokens;
             pruned tokens go to their most cosine-similar kept token in h~;  h~ <- merged rows,
             positions of the dropped tokens are removed (kept tokens keep their original positions)
-        h = h~ + (silu(f Wg^T) * (f Wu^T)) Wd^T  with  f = rmsnorm(h~)
+        h = ffn_part(h~)
     Positions are the indices 0 .. N-1 of the input sequence.  No final norm, no decoding head.
-
-    kept_override / assign_override: kept list / assignment to use instead of the oracle's own top-k /
-    argmax (for chained parity checks, so that an excused near-tie does not cascade); the oracle's own
-    choices are still returned next to them.
-    jitter: relative Gaussian perturbation applied to every value just before it is rounded for storage
-    (0 = none).  Not part of the method: a test uses it to measure how far the stored result moves when the
-    exact values move by a few float32 ulps, which is the difference any float32 implementation has to the
-    float64 one, and sizes its whole-step tolerance from that.
     Returns y [N_out, d], src_pos [N_out] and the merge layer's intermediate results."""
-    rt = _store_fn(store, jitter, jitter_seed)
+    rt = _store_fn(store)
     h = np.asarray(x, dtype=np.float64)
     N, d = h.shape
-    dh = d // H
     pos = np.arange(N, dtype=np.int64)
     dec = np.asarray(dec_idx, dtype=np.int32) if dec_idx is not None else np.zeros(0, dtype=np.int32)
     info = dict(merged=False)
     for l, blk in enumerate(blocks, start=1):
-        n = h.shape[0]
-        a = rt(rmsnorm(h, blk.attn_norm, eps))
-        q = rt(linear(a, blk.wq)).reshape(n, H, dh)
-        k = rt(linear(a, blk.wk)).reshape(n, H, dh)
-        v = rt(linear(a, blk.wv)).reshape(n, H, dh)
-        q = rt(rope(q, pos, theta)); k = rt(rope(k, pos, theta))
-        o = rt(attention(q, k, v)).reshape(n, d)
-        ht = rt(h + linear(o, blk.wo))
+        ht, q, k = attention_part(h, blk, H, pos, eps, theta, rt)
         if l == merge_layer and len(dec) > 0:
             S = _importance(q, k, dec, vis_start, V)
             kept, slot_of = _select_topk(S, keep_k)
-            own_kept = kept
-            if kept_override is not None:
-                kept = np.asarray(kept_override, dtype=np.int32)
             asg, best_cos = _assign(ht, vis_start, V, kept, return_cos=True)
-            own_assign = asg
-            if assign_override is not None:
-                asg = np.asarray(assign_override, dtype=np.int32)
             y, counts, src = _merge(ht, vis_start, V, kept, asg, mode)
             pre_merge = ht
             # rows with a single member are the kept token itself: already stored values, rounding is a no-op
             ht = rt(y)
             pos = pos[src]
-            info = dict(merged=True, S=S, kept_idx=kept, own_kept_idx=own_kept, slot_of=slot_of, assign=asg,
-                        own_assign=own_assign, best_cos=best_cos, counts=counts, pre_merge=pre_merge)
-        f = rt(rmsnorm(ht, blk.ffn_norm, eps))
-        act = rt(swiglu(linear(f, blk.w_gate), linear(f, blk.w_up)))
-        h = rt(ht + linear(act, blk.w_down))
+            info = dict(merged=True, S=S, kept_idx=kept, slot_of=slot_of, assign=asg, best_cos=best_cos, counts=counts,
+                        pre_merge=pre_merge)
+        h = ffn_part(ht, blk, eps, rt)
     info.update(y=h, src_pos=pos.astype(np.int32))
     return info

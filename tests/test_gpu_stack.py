@@ -17,6 +17,7 @@ import oracle
 from oracle import stack as OS
 from paper_2511_12280_amd import workloads as W
 import parity as P
+from stack_chain import jittered_bf16, stack_step_given
 
 pytestmark = pytest.mark.gpu
 
@@ -314,15 +315,15 @@ def test_stack_step_against_oracle(B, L, d, H, F, Pn, V, O, D, keep_k, l_star):
     # 2. the whole step against the oracle's whole step.  The oracle's own hidden states differ from the
     # GPU's by single bf16 steps here and there, which moves its scores by up to ~1e-2 relative, so its own
     # top-k may differ near the threshold: it is told the GPU's (checked) kept set and assignment.
-    ref = OS.stack_step(case["x"], _oracle_blocks(case), H, case["dec_idx"], case["vis_start"], V, keep_k, l_star,
-                        kept_override=got["kept"], assign_override=got["assign"])
+    ref = stack_step_given(case["x"], _oracle_blocks(case), H, case["dec_idx"], case["vis_start"], V, keep_k, l_star,
+                           kept=got["kept"], assign=got["assign"])
     np.testing.assert_array_equal(got["src_pos"], ref["src_pos"])
     # Tolerance: a float32 pipeline differs from the float64 one by a few float32 ulps in every value it is
     # about to store; where that crosses a bf16 rounding boundary the stored value moves by one bf16 step,
     # and later blocks carry such steps on.  The oracle measures that floor on itself (same step, every
     # stored value perturbed by 3e-7 relative before rounding); the GPU must stay within 3x of it.
-    alt = OS.stack_step(case["x"], _oracle_blocks(case), H, case["dec_idx"], case["vis_start"], V, keep_k, l_star,
-                        kept_override=got["kept"], assign_override=got["assign"], jitter=3e-7, jitter_seed=1)
+    alt = stack_step_given(case["x"], _oracle_blocks(case), H, case["dec_idx"], case["vis_start"], V, keep_k, l_star,
+                           kept=got["kept"], assign=got["assign"], store=jittered_bf16(3e-7, 1))
     rms = lambda a, b: np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2))
     y, yr = got["y"], ref["y"]
     floor, rel = rms(alt["y"], yr), rms(y, yr)
@@ -341,7 +342,8 @@ def test_stack_step_without_deciders_runs_full_length(B):
     assert got["n_out"] == case["N"]
     np.testing.assert_array_equal(got["src_pos"], np.arange(case["N"]))
     ref = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], None, case["vis_start"], case["V"], 10, 2)
-    alt = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], None, case["vis_start"], case["V"], 10, 2, jitter=3e-7)
+    alt = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], None, case["vis_start"], case["V"], 10, 2,
+                        store=jittered_bf16(3e-7))
     rms = lambda a, b: np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2))
     assert rms(got["y"], ref["y"]) <= 3.0 * rms(alt["y"], ref["y"]) + 1e-4
     # keeping every visual token is the same computation: the merge copies rows bit-exactly
@@ -356,10 +358,10 @@ def test_stack_step_without_deciders_runs_full_length(B):
 def test_stack_step_sum_mode(B):
     case = W.stack_case(78, L=2, d=256, H=4, F=512, P=8, V=120, O=12, D=6, std=1.0 / 16, gain_jitter=0.1)
     got = _run_stack(B, case, 30, 1, mode=1)
-    ref = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], case["dec_idx"], case["vis_start"], case["V"], 30, 1,
-                        kept_override=got["kept"], assign_override=got["assign"], mode="sum")
-    alt = OS.stack_step(case["x"], _oracle_blocks(case), case["H"], case["dec_idx"], case["vis_start"], case["V"], 30, 1,
-                        kept_override=got["kept"], assign_override=got["assign"], mode="sum", jitter=3e-7)
+    ref = stack_step_given(case["x"], _oracle_blocks(case), case["H"], case["dec_idx"], case["vis_start"], case["V"], 30, 1,
+                           kept=got["kept"], assign=got["assign"], mode="sum")
+    alt = stack_step_given(case["x"], _oracle_blocks(case), case["H"], case["dec_idx"], case["vis_start"], case["V"], 30, 1,
+                           kept=got["kept"], assign=got["assign"], mode="sum", store=jittered_bf16(3e-7))
     rms = lambda a, b: np.sqrt(np.mean((a - b) ** 2)) / np.sqrt(np.mean(b ** 2))
     assert rms(got["y"], ref["y"]) <= 3.0 * rms(alt["y"], ref["y"]) + 1e-4
 
@@ -512,8 +514,8 @@ def test_stack_trajectory_with_decider_updates(B):
         n_out = B.d3tom_stack_step(_dev(x), H, F, arr, L, 1, dec_idx if D else None, D, Pn, V, keep_k, 0, 1e-5, 10000.0, y, ws,
                                    kept_idx=kept, assign=asg)
         torch.cuda.synchronize()
-        over = dict(kept_override=kept.cpu().numpy(), assign_override=asg.cpu().numpy()) if D else {}
-        ref = OS.stack_step(x, _oracle_blocks(case), H, dec_ref if D else None, Pn, V, keep_k, 1, **over)
+        over = dict(kept=kept.cpu().numpy(), assign=asg.cpu().numpy()) if D else {}
+        ref = stack_step_given(x, _oracle_blocks(case), H, dec_ref if D else None, Pn, V, keep_k, 1, **over)
         assert n_out == ref["y"].shape[0] == (N - (V - keep_k) if D else N)
         merged_steps += int(D > 0)
         got = _host(y[:n_out])

@@ -228,6 +228,51 @@ def test_assign_uses_unmodified_rows():
     np.testing.assert_array_equal(a, _brute_assign(x, 0, 4, kept)[0])
 
 
+def test_cosine_hand_values_and_normalised_dot_product():
+    # oracle.cosine decides which GPU assignments count as near-ties, so it is pinned on its own:
+    # hand values (parallel, anti-parallel, orthogonal, a 3-4-5 triangle, zero rows) and numpy's
+    # normalised dot product on random rows.  A missing square root, a squared norm or a wrong clamp
+    # fails one of these.
+    x = np.array([[3.0, 4.0, 0.0], [6.0, 8.0, 0.0], [-1.5, -2.0, 0.0], [0.0, 0.0, 7.0], [3.0, 0.0, 0.0],
+                  [0.0, 0.0, 0.0]], np.float32)
+    assert oracle.cosine(x, 0, 1) == pytest.approx(1.0, abs=1e-15)        # parallel, different lengths
+    assert oracle.cosine(x, 0, 2) == pytest.approx(-1.0, abs=1e-15)       # anti-parallel
+    assert oracle.cosine(x, 0, 3) == 0.0                                  # orthogonal
+    assert oracle.cosine(x, 0, 4) == pytest.approx(0.6, abs=1e-15)        # 3 / 5
+    assert oracle.cosine(x, 4, 0) == oracle.cosine(x, 0, 4)               # symmetric
+    assert oracle.cosine(x, 0, 5) == 0.0 and oracle.cosine(x, 5, 5) == 0.0   # a zero row: 0 with everything
+    assert oracle.cosine(x, 1, 1) == pytest.approx(1.0, abs=1e-15)
+    rng = _rng(21)
+    f = (rng.standard_normal((12, 37)) * rng.uniform(0.01, 50.0, (12, 1))).astype(np.float32)
+    f64 = f.astype(np.float64)
+    for a in range(12):
+        for b in range(12):
+            ref = float(f64[a] @ f64[b]) / (np.linalg.norm(f64[a]) * np.linalg.norm(f64[b]))
+            assert oracle.cosine(f, a, b) == pytest.approx(ref, rel=1e-13, abs=1e-15)
+    # and it is the quantity oracle.assign maximises: best_cos of a pruned token is its cosine to the chosen slot
+    kept = np.array([1, 5, 8], np.int32)
+    a, bc = oracle.assign(f, 0, 12, kept, return_cos=True)
+    for m in np.setdiff1d(np.arange(12), kept):
+        assert bc[m] == pytest.approx(oracle.cosine(f, int(m), int(kept[a[m]])), rel=1e-14)
+        assert all(oracle.cosine(f, int(m), int(j)) <= bc[m] + 1e-15 for j in kept)
+
+
+def test_assign_row_sample_mask_only_skips_rows():
+    # `only` is a sampling mask for large cases: listed pruned rows get exactly the unmasked result,
+    # the other pruned rows are marked -1, kept rows are untouched
+    c = W.random_case(14, 90, 24, 1, 5, 80, 1, centres=9)
+    kept = np.sort(_rng(3).choice(80, size=11, replace=False)).astype(np.int32)
+    full, bc_full = oracle.assign(c["x"], 5, 80, kept, return_cos=True)
+    pruned = np.setdiff1d(np.arange(80), kept)
+    rows = pruned[::3]
+    part, bc_part = oracle.assign(c["x"], 5, 80, kept, return_cos=True, only=rows)
+    np.testing.assert_array_equal(part[rows], full[rows])
+    np.testing.assert_array_equal(bc_part[rows], bc_full[rows])
+    np.testing.assert_array_equal(part[kept], np.arange(11))
+    rest = np.setdiff1d(pruned, rows)
+    assert np.all(part[rest] == -1)
+
+
 # --------------------------------------------------------------------------------------
 # aggregation + removal (Section 3.2)
 # --------------------------------------------------------------------------------------
@@ -368,6 +413,56 @@ def test_attend_special_cases():
     np.testing.assert_allclose(a, o0, rtol=1e-12, atol=1e-14)
 
 
+def test_attend_row_sample_only_evaluates_listed_rows():
+    q, k, v = W.random_qkv(33, 40, 2, 8)
+    full = oracle.attend(q, k, v)
+    rows = np.array([0, 7, 39, 7], np.int32)
+    part = oracle.attend(q, k, v, rows=rows)
+    np.testing.assert_array_equal(part[[0, 7, 39]], full[[0, 7, 39]])
+    rest = np.setdiff1d(np.arange(40), rows)
+    assert np.all(part[rest] == 0.0)
+
+
+def test_attend_key_weights_equal_repeated_keys():
+    # Size-weighted attention (reading M1): a key/value row with weight c is, exactly, that row written c
+    # times.  Integer weights against the plain oracle on the physically repeated sequence; all-ones weights
+    # against the plain call; non-integer weights against torch's fp64 attention with log w as additive bias.
+    q, k, v = W.random_qkv(34, 23, 2, 8)
+    w = _rng(6).integers(1, 5, size=23)
+    rep = np.repeat(np.arange(23), w)
+    got = oracle.attend(q, k, v, key_weight=w.astype(np.float64))
+    ref = oracle.attend(np.concatenate([q, np.zeros((len(rep) - 23,) + q.shape[1:], np.float32)]), k[rep], v[rep])[:23]
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-14)
+    np.testing.assert_array_equal(oracle.attend(q, k, v, key_weight=np.ones(23)), oracle.attend(q, k, v))
+    wf = _rng(7).uniform(0.2, 9.0, size=23)
+    got = oracle.attend(q, k, v, key_weight=wf)
+    tq, tk, tv = (torch.from_numpy(a.astype(np.float64)).permute(1, 0, 2) for a in (q, k, v))
+    bias = torch.from_numpy(np.log(wf))[None, None, :].expand(2, 23, 23)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=bias).permute(1, 0, 2).numpy()
+    np.testing.assert_allclose(got, ref, rtol=1e-10, atol=1e-12)
+    # a heavier key pulls the output towards its value row
+    heavy = np.ones(23); heavy[4] = 1e9
+    np.testing.assert_allclose(oracle.attend(q, k, v, key_weight=heavy), np.broadcast_to(v[4].astype(np.float64), v.shape),
+                               rtol=1e-5, atol=1e-5)
+    with pytest.raises(ValueError):
+        oracle.attend(q, k, v, key_weight=np.zeros(23))
+
+
+def test_mean_merge_with_count_weights_keeps_the_attention_of_the_unmerged_duplicates():
+    # Why the counts are an output of the merge: when the merged tokens are exact duplicates of their kept
+    # token, MEAN aggregation returns the kept rows unchanged, and attention over the shortened sequence with
+    # the member counts as key weights equals attention over the full sequence (restricted to the kept rows).
+    rng = _rng(35)
+    base = rng.standard_normal((6, 2, 8)).astype(np.float32)
+    pick = np.array([0, 1, 2, 3, 4, 5, 2, 2, 0, 5, 5, 5, 1])
+    q, k, v = base[pick], (base * 0.7)[pick], (base + 1.0)[pick]
+    counts = np.bincount(pick, minlength=6).astype(np.float64)
+    full = oracle.attend(q, k, v)[:6]
+    short = oracle.attend(q[:6], k[:6], v[:6], key_weight=counts)
+    np.testing.assert_allclose(short, full, rtol=1e-12, atol=1e-14)
+    assert np.abs(oracle.attend(q[:6], k[:6], v[:6]) - full).max() > 1e-3      # without the weights it differs
+
+
 def test_keep_everything_chain_equals_unmerged_attention():
     wl = W.WORKLOADS["tiny_f32"]
     g = W.SampleGen(wl)
@@ -434,4 +529,24 @@ def test_deciders_over_a_whole_trajectory_partition_the_response():
         seen[d] += 1
     np.testing.assert_array_equal(seen[:n_prefix], 0)
     np.testing.assert_array_equal(seen[n_prefix:], 1)
+
+
+# --------------------------------------------------------------------------------------
+# the C file under the address and undefined-behaviour sanitizers (host only)
+# --------------------------------------------------------------------------------------
+def test_oracle_under_address_and_ub_sanitizers(tmp_path):
+    """Every entry point of oracle/d3tom_oracle.c once, on small ragged inputs, in a build with
+    -fsanitize=address,undefined (a stand-alone C driver: the sanitizer runtime wants to be loaded first, so
+    it is not dlopen-ed into this interpreter).  Any out-of-bounds access, use after free, signed overflow or
+    misaligned access aborts the driver with a non-zero status."""
+    import os, subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    drv = os.path.join(root, "tests", "oracle_sanitize_driver.c")
+    exe = tmp_path / "drive"
+    cmd = ["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-fno-omit-frame-pointer", "-static-libasan",
+           "-std=c11", "-o", str(exe), str(drv), os.path.join(root, "oracle", "d3tom_oracle.c"), "-lm"]
+    subprocess.run(cmd, check=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0")
+    res = subprocess.run([str(exe)], capture_output=True, text=True, env=env)
+    assert res.returncode == 0 and res.stdout.startswith("ok"), res.stdout + res.stderr
 

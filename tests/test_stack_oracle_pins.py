@@ -14,6 +14,7 @@ import torch.nn.functional as F
 import oracle
 from oracle import stack as OS
 from paper_2511_12280_amd import workloads as W
+from stack_chain import jittered_bf16, stack_step_given
 
 
 def _rng(seed):
@@ -215,8 +216,8 @@ def test_stack_bf16_storage_stays_close_to_exact_arithmetic():
     c = W.stack_case(4, L=4, d=64, H=2, F=128, P=4, V=24, O=6, D=4, std=0.15, gain_jitter=0.1)
     kw = dict(merge_layer=2, eps=1e-5, theta=10000.0)
     exact = OS.stack_step(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 8, store=None, **kw)
-    b16 = OS.stack_step(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 8, store="bf16",
-                        kept_override=exact["kept_idx"], assign_override=exact["assign"], **kw)
+    b16 = stack_step_given(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 8, store="bf16",
+                           kept=exact["kept_idx"], assign=exact["assign"], **kw)
     # every stored value is a bf16 number
     np.testing.assert_array_equal(OS.round_bf16(b16["y"]), b16["y"])
     err = np.sqrt(np.mean((b16["y"] - exact["y"]) ** 2)) / np.sqrt(np.mean(exact["y"] ** 2))
@@ -224,12 +225,22 @@ def test_stack_bf16_storage_stays_close_to_exact_arithmetic():
     assert 1e-4 < err < 3e-2, err
 
 
-def test_stack_overrides_are_used_and_own_choices_reported():
+def test_chain_wrapper_is_the_oracle_step_when_nothing_is_given_and_follows_what_is_given():
+    # the test-side composition (tests/stack_chain.py) calls the same pieces in the same order: with no kept
+    # list / assignment handed in it must reproduce OS.stack_step bit for bit; handed a different kept list it
+    # must use it and still report the oracle's own choice
     c = W.stack_case(5, L=2, d=64, H=2, F=64, P=2, V=16, O=4, D=2, std=0.15)
     base = OS.stack_step(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 4, merge_layer=1)
+    same = stack_step_given(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 4, 1)
+    for key in ("y", "src_pos", "S", "kept_idx", "assign", "counts"):
+        np.testing.assert_array_equal(same[key], base[key])
     other = np.sort(np.setdiff1d(np.arange(c["V"]), base["kept_idx"])[:4]).astype(np.int32)
-    alt = OS.stack_step(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 4, merge_layer=1,
-                        kept_override=other)
+    alt = stack_step_given(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 4, 1, kept=other)
     np.testing.assert_array_equal(alt["own_kept_idx"], base["kept_idx"])
     np.testing.assert_array_equal(alt["kept_idx"], other)
     assert not np.array_equal(alt["src_pos"], base["src_pos"])
+    # a jittered storage function moves stored values by whole bf16 steps only
+    jit = stack_step_given(c["x"], _blocks(c), c["H"], c["dec_idx"], c["vis_start"], c["V"], 4, 1,
+                           kept=base["kept_idx"], assign=base["assign"], store=jittered_bf16(3e-7, 1))
+    np.testing.assert_array_equal(OS.round_bf16(jit["y"]), jit["y"])
+    assert 0 < np.abs(jit["y"] - base["y"]).max() < 0.1 * np.abs(base["y"]).max()
