@@ -600,15 +600,12 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
         const int nqt = ceil_div(max_seqlen, 32);
         const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)4 * 2 * ATS_BK * dh * 2;
-        static bool attr_set_s = false;
-        if (!attr_set_s) {
-            if (hipFuncSetAttribute((const void*)attend_bf16_short_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    4 * 2 * ATS_BK * 128 * 2) != hipSuccess ||
-                hipFuncSetAttribute((const void*)attend_bf16_short_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    4 * 2 * ATS_BK * 64 * 2) != hipSuccess)
-                return D3TOM_ERR_DEVICE;
-            attr_set_s = true;
-        }
+        static PerDeviceOnce lds_setup_s;
+        if (!lds_setup_s.run([] {
+                return raise_dynamic_lds(attend_bf16_short_kernel<128>, 4 * 2 * ATS_BK * 128 * 2) &&
+                       raise_dynamic_lds(attend_bf16_short_kernel<64>, 4 * 2 * ATS_BK * 64 * 2);
+            }))
+            return D3TOM_ERR_DEVICE;
         if (dh == 128)
             D3TOM_LAUNCH(ATTEND, st, attend_bf16_short_kernel<128><<<g, 256, lds, st>>>(
                 (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
@@ -619,15 +616,12 @@ extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
         const int nqt = ceil_div(max_seqlen, ATT_BQ);
         const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)ATT_NS * 2 * ATT_BK * dh * 2;
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute((const void*)attend_bf16_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    ATT_NS * 2 * ATT_BK * 128 * 2) != hipSuccess ||
-                hipFuncSetAttribute((const void*)attend_bf16_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    ATT_NS * 2 * ATT_BK * 64 * 2) != hipSuccess)
-                return D3TOM_ERR_DEVICE;
-            attr_set = true;
-        }
+        static PerDeviceOnce lds_setup;
+        if (!lds_setup.run([] {
+                return raise_dynamic_lds(attend_bf16_kernel<128>, ATT_NS * 2 * ATT_BK * 128 * 2) &&
+                       raise_dynamic_lds(attend_bf16_kernel<64>, ATT_NS * 2 * ATT_BK * 64 * 2);
+            }))
+            return D3TOM_ERR_DEVICE;
         if (dh == 128)
             D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<128><<<g, 256, lds, st>>>(
                 (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <mutex>
 #include "../../include/d3tom.h"
 
 namespace d3tom {
@@ -91,6 +92,25 @@ __host__ __device__ __forceinline__ size_t align_up(size_t a, size_t b) { return
 
 // host-side argument checks
 inline bool aligned16(const void* p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// One-time set-up per device (raising a kernel's dynamic LDS limit): safe when several host threads enter
+// the same entry point at once, and repeated for every device the library is used on.
+struct PerDeviceOnce {
+    static constexpr int MAX_DEVICES = 64;
+    std::once_flag flag[MAX_DEVICES];
+    bool ok[MAX_DEVICES] = {};
+    template <typename Fn>
+    bool run(Fn&& fn) {
+        int dev = -1;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return false;
+        std::call_once(flag[dev], [&] { ok[dev] = fn(); });
+        return ok[dev];
+    }
+};
+template <typename K>
+inline bool raise_dynamic_lds(K kernel, int bytes) {
+    return hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) == hipSuccess;
+}
 
 // ---- optional per-kernel timing (d3tom_profile_*): HIP events around each launch when enabled ----
 namespace prof {

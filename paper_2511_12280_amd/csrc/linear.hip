@@ -229,13 +229,8 @@ template <int TM, int EPI>
 int launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out, int out_chunk,
                   int ksplit, int col0, int col_end, hipStream_t st) {
     using C = LinCfg<TM>;
-    static bool attr_done = false;       // per instantiation; the attribute only has to be set once per process
-    if (!attr_done) {
-        if (hipFuncSetAttribute((const void*)linear_bf16_kernel<TM, EPI>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                C::LDS) != hipSuccess)
-            return D3TOM_ERR_DEVICE;
-        attr_done = true;
-    }
+    static PerDeviceOnce lds_setup;      // per instantiation
+    if (!lds_setup.run([] { return raise_dynamic_lds(linear_bf16_kernel<TM, EPI>, C::LDS); })) return D3TOM_ERR_DEVICE;
     const int out_bn = (EPI == LIN_SWIGLU) ? 64 : 128;
     const int NRT = ceil_div(M, C::BM), NCT = ceil_div(col_end - col0, out_bn);
     const int cpx = ceil_div(NCT, 8);

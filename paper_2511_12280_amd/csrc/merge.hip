@@ -5,15 +5,16 @@
 //   norms     1 / ||row|| of every KEPT row of the similarity features (1 wave / row): the argmax over
 //             kept slots of dot / (|m| |k|) does not depend on |m|, the pruned row's own norm; the same
 //             waves write the ascending list of pruned visual tokens (the gaps of the ascending kept_idx)
+//             and initialise the token -> (best value, slot) table
 //   cosine    pruned x kept similarity GEMM on MFMA 32x32x16 bf16 with the argmax fused into the
 //             epilogue: only (best value, best slot) per (pruned row, 128-slot column tile) ever
-//             leaves the registers; the M x k matrix is never written
-//   assign    argmax across column tiles (ascending, strict '>' : ties go to the lowest slot) for every
-//             pruned token, own slot for every kept token -> token -> slot table   (1 thread / token)
-//   scatter   one workgroup per OUTPUT row: a merged row scans the token -> slot table for its members
-//             (ascending token order), streams them with 16-byte loads and accumulates in float32 in
-//             that order, other rows are copied; one store per element, no atomics, so the result is
-//             bit-reproducible
+//             leaves the registers, as ONE 64-bit integer atomic max on the row's table entry (value in
+//             the high word as an order-preserving integer, 2^32-1-slot in the low word: the maximum is
+//             the best cosine, the lowest slot among equals, whatever order the tiles arrive in, so the
+//             result is bit-reproducible); the M x k matrix is never written
+//   scatter   one workgroup per OUTPUT row: a merged row scans the table for its members (ascending
+//             token order), streams them with 16-byte loads and accumulates in float32 in that order,
+//             other rows are copied; one store per element, no float atomics
 //
 // All similarities are taken on the rows as given (assignment first, aggregation afterwards).
 #include "common.hpp"
@@ -27,22 +28,36 @@ constexpr int COS_BK = 64;         // contraction elements per LDS stage
 // split-K partial products: at most COS_SPLIT_BLOCKS (tile, k-slice) blocks of 64 x 128 floats
 constexpr int COS_SPLIT_BLOCKS = 256;
 struct MergeWs {
-    size_t pruned_off, rnorm_off, part_off, mem_off, dots_off, total;
-    int NCT;
+    size_t pruned_off, rnorm_off, table_off, dots_off, total;
+    int VP;                    // table entries per sample
 };
 __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
     MergeWs w;
-    w.NCT = ceil_div(max_V, COS_BN);
+    w.VP = (int)align_up((size_t)max_V, 4);
     size_t o = 0;
     w.pruned_off = o; o += align_up((size_t)B * max_V * 4, 256);
     w.rnorm_off = o;  o += align_up((size_t)B * max_V * 4, 256);
-    w.part_off = o;   o += align_up((size_t)B * w.NCT * max_V * 8, 256);
-    w.mem_off = o;    o += align_up((size_t)B * align_up((size_t)max_V, 4) * 4, 256);   // token -> slot table, rows of 4-entry groups
+    w.table_off = o;  o += align_up((size_t)B * w.VP * 8, 256);     // token -> (best value, slot) table
     w.dots_off = o;   o += (size_t)COS_SPLIT_BLOCKS * 64 * 128 * sizeof(float);
     w.total = o;
     return w;
 }
 size_t merge_ws_bytes(int B, int max_V) { return merge_ws_layout(B, max_V).total; }
+
+// Table entry of a visual token: (order-preserving integer image of its best value so far) << 32 | (2^32-1 - slot).
+// Unsigned comparison of entries = (value, then lower slot); 0 = nothing yet (below every real entry); a kept
+// token holds the largest high word with its own slot and is never a target of an update.
+typedef unsigned long long table_t;
+__device__ __forceinline__ uint32_t value_key(float f) {       // ascending uint order == ascending float order
+    const uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ table_t table_entry(float value, int slot) {
+    return ((table_t)value_key(value) << 32) | (table_t)(0xFFFFFFFFu - (uint32_t)slot);
+}
+__device__ __forceinline__ table_t table_entry_kept(int slot) {
+    return ((table_t)0xFFFFFFFFu << 32) | (table_t)(0xFFFFFFFFu - (uint32_t)slot);
+}
 
 struct SampleGeom { int tok0, N, vs, V, k, M; };
 __device__ __forceinline__ SampleGeom sample_geom(int b, const int32_t* seq_off, const int32_t* vis_start,
@@ -57,17 +72,18 @@ __device__ __forceinline__ SampleGeom sample_geom(int b, const int32_t* seq_off,
     return s;
 }
 
-// ---- norms + pruned list ------------------------------------------------------------------------
+// ---- norms + pruned list + table init --------------------------------------------------------------
 // One wave per kept slot r computes 1 / ||row|| of that slot's token.  The same wave also writes the
 // piece of the ascending pruned list that lies in front of its token: kept_idx is ascending, so the
 // pruned tokens j between kept_idx[r-1] and kept_idx[r] have exactly r kept tokens before them and sit
 // at positions j - r of the list (the wave of the last slot also writes the piece behind its token).
-// No scan, no extra workgroup.
+// No scan, no extra workgroup.  The table entries of the same tokens are set on the way: "nothing yet"
+// for the pruned ones, its own slot for the kept one.
 template <typename T>
 __global__ __launch_bounds__(256) void merge_norms_kernel(
     const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, float* __restrict__ rnorm, int32_t* __restrict__ pruned) {
+    int max_V, int max_keep, float* __restrict__ rnorm, int32_t* __restrict__ pruned, table_t* __restrict__ table, int VP) {
     const int b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int r = blockIdx.x * 4 + (threadIdx.x >> 6);      // kept slot
@@ -77,12 +93,14 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
     const int j = min(max(kp[r], 0), s.V - 1);
     {
         int32_t* pr = pruned + (size_t)b * max_V;
+        table_t* tab = table + (size_t)b * VP;
         const int lo = (r == 0) ? -1 : min(max(kp[r - 1], 0), s.V - 1);
         // positions are >= 0 whenever kept_idx is ascending and free of repeats; the guard only keeps an
         // invalid list from writing in front of the array
-        for (int t = lo + 1 + lane; t < j; t += 64) if (t >= r) pr[t - r] = t;
+        for (int t = lo + 1 + lane; t < j; t += 64) { tab[t] = 0; if (t >= r) pr[t - r] = t; }
         if (r == s.k - 1)
-            for (int t = j + 1 + lane; t < s.V; t += 64) if (t >= s.k) pr[t - s.k] = t;
+            for (int t = j + 1 + lane; t < s.V; t += 64) { tab[t] = 0; if (t >= s.k) pr[t - s.k] = t; }
+        if (lane == 0) tab[j] = table_entry_kept(r);
     }
     const T* row = f + (size_t)(s.tok0 + s.vs + j) * d;
     constexpr int EPC = 16 / sizeof(T);       // elements per 16-byte chunk
@@ -123,9 +141,11 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 // position p of row r is chunk p ^ ((r >> 1) & 7) of that row (the lane picks its global address
 // accordingly), which spreads the MFMA operand reads of 16 consecutive rows over all 64 banks.
 //
-// Workgroup ids are mapped to tiles per XCD: ids are dealt round-robin to the 8 XCDs, each XCD
-// owns a rectangular block of R x C tiles, so its private L2 only ever sees R row tiles and C column
-// tiles of the operands.
+// Workgroup ids are mapped to tiles per XCD: ids are dealt round-robin to the 8 XCDs by the hardware.  The
+// tiles of a sample are numbered band by band (RB row tiles high, column-major inside a band) and that
+// sequence is cut into 8 runs of equal length, one per XCD: every XCD gets the same number of tiles
+// (a rectangle per XCD leaves some XCDs with more tiles than they have CUs while others idle), and a
+// run covers a compact block of about RB x (run / RB) tiles, so its private L2 sees few operand rows.
 // The loads are buffer loads: each lane's byte offset (row and swizzled chunk) is fixed for the whole
 // sweep and the k-slice moves through the scalar offset, so a stage costs no address arithmetic.
 constexpr int COS_NS = 4;
@@ -134,8 +154,8 @@ template <int TM>
 __global__ __launch_bounds__(512) void cos_argmax_bf16(
     const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
-    float2* __restrict__ part, int XC, int R, int C, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch) {
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
+    table_t* __restrict__ table, int VP, int per, int RB, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BM = TM * 64;
     constexpr int STAGE = (BM + COS_BN) * 128;          // bytes per ring stage (64 bf16 = 128 B per row)
@@ -145,10 +165,17 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     extern __shared__ __attribute__((aligned(16))) char ring[];
     __shared__ float rnB[COS_BN];
 
-    const int per = 8 * R * C;
-    const int b = blockIdx.x / per;
-    const int rem = blockIdx.x % per, xcd = rem & 7, li = rem >> 3;
-    const int rt = (xcd / XC) * R + li / C, ct = (xcd % XC) * C + li % C;
+    // blockIdx.x = sample * 8 * per + id; id & 7 is the XCD the hardware puts the workgroup on
+    const int b = blockIdx.x / (8 * per);
+    const int id = blockIdx.x % (8 * per);
+    const int t_lin = (id & 7) * per + (id >> 3);
+    if (t_lin >= nrt_launch * nct_launch) return;
+    int rt, ct;
+    {
+        const int band = RB * nct_launch, nfull = nrt_launch / RB;
+        if (t_lin < nfull * band) { const int rem = t_lin % band; rt = (t_lin / band) * RB + rem % RB; ct = rem / RB; }
+        else { const int t2 = t_lin - nfull * band, rl = nrt_launch - nfull * RB; rt = nfull * RB + t2 % rl; ct = t2 / rl; }
+    }
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     if (rt * BM >= s.M || ct * COS_BN >= s.k) return;
 
@@ -273,7 +300,7 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     if (ksplit > 1) {
         // partial products of this k-slice: block (slice, tile) of BM x 128 floats, summed by cos_reduce_argmax
         const int tile_id = (b * nrt_launch + rt) * nct_launch + ct;
-        const int n_tiles = (int)(gridDim.x / (8 * R * C)) * nrt_launch * nct_launch;
+        const int n_tiles = (int)(gridDim.x / (8 * per)) * nrt_launch * nct_launch;
         float* blk = dots + ((size_t)blockIdx.y * n_tiles + tile_id) * (BM * COS_BN);
         if (loader) return;
 #pragma unroll
@@ -337,7 +364,10 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
         const bool take = (ov > best) | ((ov == best) & (oi < bidx));
         best = take ? ov : best; bidx = take ? oi : bidx;
         const int p = rt * BM + row;
-        if (half == 0 && p < s.M) part[((size_t)b * NCT + ct) * max_V + p] = make_float2(best, __int_as_float(bidx));
+        if (half == 0 && p < s.M) {
+            const int tok = min(max(pr[p], 0), s.V - 1);
+            atomicMax(table + (size_t)b * VP + tok, table_entry(best, bidx));
+        }
     }
 #endif
 }
@@ -346,29 +376,19 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
 // Used when the similarity matrix has too few tiles to occupy the chip (short sequences): the GEMM is
 // then cut along the contraction instead, and one wave per pruned row finishes the job here.  Slices
 // are added in ascending order and slots are visited in ascending order, so the result is deterministic
-// and ties go to the lowest slot.  The wave writes the token -> slot table entry (and `assign`) itself, and
-// waves M .. V-1 enter the kept tokens, so this launch also stands in for merge_assign_kernel.
+// and ties go to the lowest slot.  The wave writes the row's table entry itself.
 __global__ __launch_bounds__(256) void cos_reduce_argmax(
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
-    const int32_t* __restrict__ vis_off, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
+    const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
     const float* __restrict__ dots, int ksplit, int n_tiles, int nrt_launch, int nct_launch,
-    int32_t* __restrict__ assign_out, int32_t* __restrict__ slot_of_tok) {
+    table_t* __restrict__ table, int VP) {
     constexpr int BM = 64;
     const int b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int p = blockIdx.x * 4 + wave;
-    if (s.k <= 0 || p >= s.V) return;
-    int32_t* table = slot_of_tok + (size_t)b * align_up((size_t)max_V, 4);
-    if (p >= s.M) {                                        // kept slot p - M: its own token
-        if (lane == 0) {
-            const int tok = min(max(kept_idx[kept_off[b] + p - s.M], 0), s.V - 1);
-            table[tok] = p - s.M;
-            if (assign_out) assign_out[vis_off[b] + tok] = p - s.M;
-        }
-        return;
-    }
+    if (s.k <= 0 || p >= s.M) return;
     const float* rn = rnorm + (size_t)b * max_V;
     const int rt = p / BM, lr = p % BM;
     const int nct = (s.k + COS_BN - 1) / COS_BN;
@@ -407,8 +427,7 @@ __global__ __launch_bounds__(256) void cos_reduce_argmax(
     if (lane == 0) {
         const int slot = min(max(bidx, 0), s.k - 1);
         const int tok = min(max(pruned[(size_t)b * max_V + p], 0), s.V - 1);
-        table[tok] = slot;
-        if (assign_out) assign_out[vis_off[b] + tok] = slot;
+        table[(size_t)b * VP + tok] = table_entry(best, slot);
     }
 }
 
@@ -417,8 +436,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void cos_argmax_generic(
     const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm, int NCT,
-    float2* __restrict__ part) {
+    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
+    table_t* __restrict__ table, int VP) {
     const int p = blockIdx.x, b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     if (p >= s.M) return;
@@ -446,49 +465,16 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
             const float2 c2 = red[w];
             if (c2.x > a.x || (c2.x == a.x && __float_as_int(c2.y) < __float_as_int(a.y))) a = c2;
         }
-        part[((size_t)b * NCT + 0) * max_V + p] = a;
+        table[(size_t)b * VP + m] = table_entry(a.x, min(max(__float_as_int(a.y), 0), s.k - 1));
     }
-}
-
-// ---- assignment: argmax over column tiles -> destination slot of every visual token ----------------
-// One thread per visual token: entry i < M is the i-th pruned token (best slot over the column tiles,
-// ascending tiles and strict '>' so that the lowest slot wins ties), entry i >= M is kept slot i - M
-// (its own token).  slot_of_tok[b][token] is what the scatter kernel scans.
-__global__ __launch_bounds__(256) void merge_assign_kernel(
-    const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
-    const int32_t* __restrict__ vis_off, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, const int32_t* __restrict__ pruned, const float2* __restrict__ part, int NCT, int tiled,
-    int32_t* __restrict__ assign_out, int32_t* __restrict__ slot_of_tok) {
-    const int b = blockIdx.y;
-    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (s.k <= 0 || i >= s.V) return;
-    int tok, slot;
-    if (i < s.M) {
-        const int nct = tiled ? (s.k + COS_BN - 1) / COS_BN : 1;
-        const float2* pb = part + (size_t)b * NCT * max_V;
-        float bv = -INFINITY; int bi = 0;
-        for (int c0 = 0; c0 < nct; c0 += 16) {             // 16 independent loads in flight
-            float2 a[16];
-#pragma unroll
-            for (int w = 0; w < 16; ++w) a[w] = (c0 + w < nct) ? pb[(size_t)(c0 + w) * max_V + i] : make_float2(-INFINITY, 0.f);
-#pragma unroll
-            for (int w = 0; w < 16; ++w) if (a[w].x > bv) { bv = a[w].x; bi = __float_as_int(a[w].y); }
-        }
-        slot = min(max(bi, 0), s.k - 1);
-        tok = min(max(pruned[(size_t)b * max_V + i], 0), s.V - 1);
-    } else {
-        slot = i - s.M;
-        tok = min(max(kept_idx[kept_off[b] + slot], 0), s.V - 1);
-    }
-    slot_of_tok[(size_t)b * align_up((size_t)max_V, 4) + tok] = slot;
-    if (assign_out) assign_out[vis_off[b] + tok] = slot;
 }
 
 // ---- scatter-average + compaction ----------------------------------------------------------
 // One workgroup per output row.  A merged row first finds its members: the four waves scan the
-// token -> slot table of the sample (a quarter each, coalesced), keep the matches in ascending token
-// order (ballot + popcount, no atomics) and the four pieces are joined into one list in LDS.  The member
+// table of the sample (a quarter each, coalesced; the low word of an entry names the slot, and the kept
+// token's own entry makes it a member like the others), keep the matches in ascending token
+// order (ballot + popcount, no atomics) and the four pieces are joined into one list in LDS; the
+// workgroup of a slot also writes the slot into `assign` for each of its members.  The member
 // rows are then streamed four at a time so that eight 16-byte loads per thread are in flight;
 // accumulation order is ascending token index, so the result does not depend on the unrolling.  A slot
 // with more members than the LDS list holds is processed in windows of SCAT_LIST members (re-scan).
@@ -498,8 +484,9 @@ template <typename T, int CPT>     // CPT: 16-byte chunks per thread per pass
 __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const T* __restrict__ x0, const T* __restrict__ x1, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
-    int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const int32_t* __restrict__ slot_of_tok,
-    T* __restrict__ y0, T* __restrict__ y1, int32_t* __restrict__ counts_out, int32_t* __restrict__ src_pos_out, int nslice) {
+    int max_V, int max_keep, int mode, const int32_t* __restrict__ out_off, const table_t* __restrict__ table, int VP,
+    const int32_t* __restrict__ vis_off, T* __restrict__ y0, T* __restrict__ y1, int32_t* __restrict__ assign_out,
+    int32_t* __restrict__ counts_out, int32_t* __restrict__ src_pos_out, int nslice) {
     constexpr int EPC = 16 / sizeof(T);
     // a row may be cut into nslice column slices, one workgroup each (few output rows: more workgroups)
     const int o = blockIdx.x / nslice, slice = blockIdx.x % nslice, b = blockIdx.y;
@@ -509,6 +496,7 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     T* __restrict__ y = blockIdx.z ? y1 : y0;
     int32_t* counts = (blockIdx.z || slice) ? nullptr : counts_out;
     int32_t* src_pos = (blockIdx.z || slice) ? nullptr : src_pos_out;
+    int32_t* assign = (blockIdx.z || slice || !assign_out) ? nullptr : assign_out + vis_off[b];
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     const int N_m = s.N - s.M;
     if (o >= N_m) return;
@@ -521,38 +509,35 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     const int c_per = (nch + nslice - 1) / nslice;
     const int c_lo = slice * c_per, c_hi = min(nch, c_lo + c_per);          // this workgroup's 16-byte chunks
     int src = -1, len = 1, r = 0;
-    // token -> slot table of this sample, read four entries per lane; a wave takes a contiguous part
-    // of it (a multiple of 256 entries so that every lane takes part in each ballot)
-    const int4* sot4 = reinterpret_cast<const int4*>(slot_of_tok + (size_t)b * align_up((size_t)max_V, 4));
-    const int part_len = ((s.V + 1023) >> 10) << 8;
+    // table of this sample, read two entries (16 bytes) per lane; a wave takes a contiguous part of it
+    // (a multiple of 128 entries so that every lane takes part in each ballot)
+    const uint4* tab2 = reinterpret_cast<const uint4*>(table + (size_t)b * VP);
+    const int part_len = ((s.V + 511) >> 9) << 7;
     const int e0 = wave * part_len;
-    const int n_it = part_len >> 8;
+    const int n_it = part_len >> 7;
     int wbase = 0;                                         // members found by the waves before this one
     bool fits = true;
+    uint32_t want = 0;                                     // low word of the entries of this row's slot
     // scan this wave's part: fn(token, ordinal among this wave's matches) for every match, ascending
     auto scan = [&](auto&& fn) {
         int cnt = 0;
         for (int it0 = 0; it0 < n_it; it0 += 4) {
-            int4 v[4];
+            uint4 v[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int i = e0 + (it0 + u) * 256 + lane * 4;
-                v[u] = (it0 + u < n_it && i < s.V) ? sot4[i >> 2] : make_int4(-1, -1, -1, -1);
+                const int i = e0 + (it0 + u) * 128 + lane * 2;
+                v[u] = (it0 + u < n_it && i < s.V) ? tab2[i >> 1] : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int i = e0 + (it0 + u) * 256 + lane * 4;
-                const bool m0 = v[u].x == r, m1 = (v[u].y == r) && (i + 1 < s.V), m2 = (v[u].z == r) && (i + 2 < s.V),
-                           m3 = (v[u].w == r) && (i + 3 < s.V);
+                const int i = e0 + (it0 + u) * 128 + lane * 2;
+                const bool m0 = (v[u].x == want) && (i < s.V), m1 = (v[u].z == want) && (i + 1 < s.V);
                 const unsigned long long lt = (1ull << lane) - 1ull;
-                const unsigned long long b0 = __builtin_amdgcn_ballot_w64(m0), b1 = __builtin_amdgcn_ballot_w64(m1),
-                                         b2 = __builtin_amdgcn_ballot_w64(m2), b3 = __builtin_amdgcn_ballot_w64(m3);
-                int ord = cnt + __popcll(b0 & lt) + __popcll(b1 & lt) + __popcll(b2 & lt) + __popcll(b3 & lt);
+                const unsigned long long b0 = __builtin_amdgcn_ballot_w64(m0), b1 = __builtin_amdgcn_ballot_w64(m1);
+                int ord = cnt + __popcll(b0 & lt) + __popcll(b1 & lt);
                 if (m0) fn(i, ord++);
                 if (m1) fn(i + 1, ord++);
-                if (m2) fn(i + 2, ord++);
-                if (m3) fn(i + 3, ord++);
-                cnt += __popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3);
+                cnt += __popcll(b0) + __popcll(b1);
             }
         }
         return cnt;
@@ -561,7 +546,11 @@ __global__ __launch_bounds__(256) void merge_scatter_kernel(
     else if (o >= s.vs + s.k) src = o + s.M;
     else {
         r = o - s.vs;
-        const int cnt = scan([&](int tok, int ord) { if (ord < SCAT_WAVE) stage[wave][ord] = tok; });
+        want = 0xFFFFFFFFu - (uint32_t)r;
+        const int cnt = scan([&](int tok, int ord) {
+            if (ord < SCAT_WAVE) stage[wave][ord] = tok;
+            if (assign) assign[tok] = r;
+        });
         if (lane == 0) wcnt[wave] = cnt;
         __syncthreads();
         len = wcnt[0] + wcnt[1] + wcnt[2] + wcnt[3];
@@ -704,30 +693,27 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
     char* wsb = (char*)ws;
     int32_t* pruned = (int32_t*)(wsb + w.pruned_off);
     float* rnorm = (float*)(wsb + w.rnorm_off);
-    float2* part = (float2*)(wsb + w.part_off);
-    int32_t* mem = (int32_t*)(wsb + w.mem_off);
+    table_t* table = (table_t*)(wsb + w.table_off);
 
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)cos_argmax_bf16<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                COS_NS * (64 + COS_BN) * 128) != hipSuccess ||
-            hipFuncSetAttribute((const void*)cos_argmax_bf16<2>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                COS_NS * (128 + COS_BN) * 128) != hipSuccess)
-            return D3TOM_ERR_DEVICE;
-        attr_set = true;
-    }
+    static PerDeviceOnce lds_setup;
+    if (!lds_setup.run([] {
+            return raise_dynamic_lds(cos_argmax_bf16<1>, COS_NS * (64 + COS_BN) * 128) &&
+                   raise_dynamic_lds(cos_argmax_bf16<2>, COS_NS * (128 + COS_BN) * 128);
+        }))
+        return D3TOM_ERR_DEVICE;
 
     const dim3 gn(ceil_div(max_keep, 4), B);
     if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>(
-            (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned));
+            (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned,
+            table, w.VP));
     else
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<float><<<gn, 256, 0, st>>>(
-            (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned));
+            (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned,
+            table, w.VP));
 
-    bool split = false;
     const bool mfma = (dt == D3TOM_BF16) && (d_sim % COS_BK == 0) && ((size_t)max_V * d_sim * 2 < ((size_t)1 << 31));
-    if (mfma) {
+    if (mfma && max_pruned > 0) {
         const int nct = ceil_div(max_keep, COS_BN);
         // as long as the 64-row tiles still fit one round of the 256 CUs they finish sooner than half as many
         // 128-row tiles (a 64-row tile's k-loop is ~0.7 of a 128-row tile's)
@@ -735,58 +721,47 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         // too few 64 x 128 tiles for 256 CUs (short sequences): cut the contraction into k-slices as well
         int ksplit = 1;
         if (TM == 1) {
-            const long tiles = (long)ceil_div(max_pruned > 0 ? max_pruned : 1, 64) * nct * B;
+            const long tiles = (long)ceil_div(max_pruned, 64) * nct * B;
             const int stages = d_sim / COS_BK;
             if (tiles <= COS_SPLIT_BLOCKS / 2) {
                 ksplit = 16;
                 while (ksplit > 1 && (tiles * ksplit > COS_SPLIT_BLOCKS || stages % ksplit || stages / ksplit < COS_NS)) ksplit >>= 1;
             }
         }
-        split = ksplit > 1;
         const int BM = TM * 64;
-        const int nrt = ceil_div(max_pruned > 0 ? max_pruned : 1, BM);
-        // XCD grid XR x XC (8 XCDs): fewest tiles per XCD first, then fewest operand rows per XCD
-        int XC = 1, R = ceil_div(nrt, 8), C = nct;
-        long best = -1;
-        for (int xc = 1; xc <= 8; xc <<= 1) {
-            const int xr = 8 / xc, r = ceil_div(nrt, xr), c = ceil_div(nct, xc);
-            const long cost = (long)r * c * 100000 + (long)r * BM + (long)c * COS_BN;
-            if (best < 0 || cost < best) { best = cost; XC = xc; R = r; C = c; }
-        }
-        const dim3 g((unsigned)(8 * R * C * B), (unsigned)ksplit);
+        const int nrt = ceil_div(max_pruned, BM);
+        // tiles of a sample in 8 equal runs (one per XCD); bands about as high as a run's block is wide
+        const int per = ceil_div(nrt * nct, 8);
+        int RB = 1;
+        while ((RB + 1) * (RB + 1) <= per) ++RB;
+        if (RB > nrt) RB = nrt;
+        const dim3 g((unsigned)(8 * per * B), (unsigned)ksplit);
         float* dots = (float*)(wsb + w.dots_off);
         const size_t lds = (size_t)COS_NS * (BM + COS_BN) * 128;
         if (TM == 1)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part, XC, R, C, ksplit, dots, nrt, nct));
+                rnorm, table, w.VP, per, RB, ksplit, dots, nrt, nct));
         else
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part, XC, R, C, 1, dots, nrt, nct));
-        if (split) {
-            const dim3 gr(ceil_div(max_V, 4), B);
+                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct));
+        if (ksplit > 1) {
+            const dim3 gr(ceil_div(max_pruned, 4), B);
             D3TOM_LAUNCH(COS_REDUCE, st, cos_reduce_argmax<<<gr, 256, 0, st>>>(
-                seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, rnorm, dots, ksplit,
-                nrt * nct * B, nrt, nct, assign, mem));
+                seq_off, vis_start, vis_count, kept_off, max_V, max_keep, pruned, rnorm, dots, ksplit,
+                nrt * nct * B, nrt, nct, table, w.VP));
         }
-    } else {
-        const dim3 g(max_V, B);
+    } else if (max_pruned > 0) {
+        const dim3 g(max_pruned, B);
         if (dt == D3TOM_BF16)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_generic<uint16_t><<<g, 256, 0, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part));
+                rnorm, table, w.VP));
         else
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_generic<float><<<g, 256, 0, st>>>(
                 (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, w.NCT, part));
-    }
-
-    if (!split) {                                        // the split-K reduce has written the table already
-        const dim3 ga(ceil_div(max_V, 256), B);
-        D3TOM_LAUNCH(MERGE_ASSIGN, st, merge_assign_kernel<<<ga, 256, 0, st>>>(
-            seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off, max_V, max_keep, pruned, part, w.NCT, mfma ? 1 : 0,
-            assign, mem));
+                rnorm, table, w.VP));
     }
 
     // few output rows (short sequences): two workgroups per row, half a row each, so that more CUs stream
@@ -796,7 +771,7 @@ static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
 #define D3TOM_SCATTER(TYPE, CPT)                                                                                        \
     D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<TYPE, CPT><<<gs, 256, 0, st>>>(                                \
         (const TYPE*)x0, (const TYPE*)x1, d, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, mode,   \
-        out_off, mem, (TYPE*)y0, (TYPE*)y1, counts, src_pos, nslice))
+        out_off, table, w.VP, vis_off, (TYPE*)y0, (TYPE*)y1, assign, counts, src_pos, nslice))
     if (dt == D3TOM_BF16) { if (nslice == 2) D3TOM_SCATTER(uint16_t, 1); else D3TOM_SCATTER(uint16_t, 2); }
     else                  { if (nslice == 2) D3TOM_SCATTER(float, 1); else D3TOM_SCATTER(float, 2); }
 #undef D3TOM_SCATTER

@@ -175,13 +175,8 @@ extern "C" int d3tom_select_topk(const float* scores, int B, const int32_t* scor
     if (!scores || !score_off || !keep_k || !kept_off || !kept_idx || !slot_of) return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || max_V < 1) return D3TOM_ERR_INVALID_ARG;
     if (max_V > D3TOM_MAX_VISUAL) return D3TOM_ERR_UNSUPPORTED;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)topk_select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                D3TOM_MAX_VISUAL * 4) != hipSuccess)
-            return D3TOM_ERR_DEVICE;
-        attr_set = true;
-    }
+    static PerDeviceOnce lds_setup;
+    if (!lds_setup.run([] { return raise_dynamic_lds(topk_select_kernel, D3TOM_MAX_VISUAL * 4); })) return D3TOM_ERR_DEVICE;
     hipStream_t st = (hipStream_t)stream;
     D3TOM_LAUNCH(TOPK_SELECT, st, topk_select_kernel<<<B, TOPK_THREADS, (size_t)max_V * 4, st>>>(
         scores, score_off, keep_k, kept_off, max_V, kept_idx, slot_of));

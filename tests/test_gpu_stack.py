@@ -333,6 +333,7 @@ def test_stack_step_against_oracle(B, L, d, H, F, Pn, V, O, D, keep_k, l_star):
           f"(floor {np.abs(alt['y'] - yr).max():.2e}), score rel {rel_s:.2e} (floor {floor_s:.2e})")
     assert rel <= 3.0 * floor + 1e-4, (rel, floor)
     assert np.abs(y - yr).max() <= 3.0 * np.abs(alt["y"] - yr).max() + 2.0 ** -8, np.abs(y - yr).max()
+    assert (np.abs(y - yr) - _whole_step_elementwise_bound(yr, L)).max() <= 0
     assert rel_s <= 3.0 * floor_s + 1e-3, (rel_s, floor_s)
 
 
@@ -437,13 +438,51 @@ def test_stack_full_size_properties(B):
     assert torch.equal(again["y"], merged["y"])
 
 
+def _whole_step_elementwise_bound(ref, n_blocks):
+    """Element-wise bound of a whole step.  The last rounding of an element can differ by one bf16 step:
+    2^-7 |ref|.  Everything before it reaches the element through normalisations and matrix products, which
+    spread the rounding differences of earlier stored tensors over all elements of a row: a stored tensor
+    carries a relative rms rounding error of 2^-9 / sqrt(3), a step crosses about ten stored tensors per block
+    (normalised rows, q, k, v, attention output, post-attention state, merged rows, normalised rows, activation,
+    block output), and independent errors add in quadrature: sigma = 2^-9 / sqrt(3) * sqrt(10 L) relative to the
+    rms of the output (5e-3 for two blocks, which is the floor the oracle measures on itself).  An element's
+    share of that is close to Gaussian; 8 sigma covers the largest of a few million elements."""
+    rms = np.sqrt(np.mean(ref * ref)) + 1e-30
+    sigma = 2.0 ** -9 / np.sqrt(3.0) * np.sqrt(10.0 * n_blocks)
+    return 2.0 ** -7 * np.abs(ref) + 8.0 * sigma * rms
+
+
 def test_stack_full_size_two_blocks_against_oracle(B):
-    """Two full-size blocks with the merge inside the first (3773 -> 493 tokens) against the oracle."""
+    """Two full-size blocks with the merge inside the first (3773 -> 493 tokens) against the oracle: the merge
+    layer stage by stage on the values the GPU itself fed to it (rebuilt through the same entry points), at the
+    bars of the hot path (scores 1e-3 relative, kept set and assignment exact up to 1e-3 near-ties, every row
+    checked); then the whole step, element by element and in relative rms."""
     cfg, inp, N, ws = _full_size(B, 2)
     H, V, P_ = cfg["H"], cfg["V"], cfg["P"]
+    d, F, dh = cfg["d"], cfg["F"], cfg["d"] // cfg["H"]
     k = B.d3tom_keep_count(V, cfg["keep_ratio"])
     got = _step_full(B, cfg, inp, N, ws, 2, 1, 8, k)
-    d, F = cfg["d"], cfg["F"]
+    # 1. what the merge layer of block 1 saw on the GPU: rotated q, k and the post-attention hidden state
+    blk = inp["blocks"][0]
+    x_dev = inp["x"]
+    a = torch.empty_like(x_dev)
+    B.d3tom_rmsnorm(x_dev, blk["attn_norm"], cfg["eps"], a)
+    qkv = torch.empty(3, N, d, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(a, blk["w_qkv"], B.D3TOM_LINEAR_PLAIN, qkv, out_chunk=d)
+    qd, kd, vd = (qkv[i].view(N, H, dh) for i in range(3))
+    B.d3tom_rope(qd, kd, torch.arange(N, dtype=torch.int32, device="cuda"), cfg["theta"])
+    o = torch.empty(N, H, dh, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_attend(qd, kd, vd, torch.tensor([0, N], dtype=torch.int32, device="cuda"), N, 1.0 / np.sqrt(dh), o, B.workspace(256))
+    ht = torch.empty(N, d, dtype=torch.bfloat16, device="cuda")
+    B.d3tom_linear(o.view(N, d), blk["w_o"], B.D3TOM_LINEAR_RESIDUAL, ht, residual=x_dev)
+    torch.cuda.synchronize()
+    qh, kh, hth = (t.float().cpu().numpy() for t in (qd, kd, ht))
+    S_ref = oracle.importance(qh, kh, got["dec"], P_, V)
+    rel_s = P.check_scores(got["S"], S_ref)
+    slot = np.full(V, -1, np.int32); slot[got["kept"]] = np.arange(k)
+    n_kept = P.check_kept(got["kept"], slot, S_ref, k)
+    n_asg = P.check_assign(got["assign"], hth, P_, V, got["kept"])          # every pruned row
+    # 2. the whole step against the oracle's whole step on the GPU's (checked) kept set and assignment
     blocks = []
     for b in inp["blocks"][:2]:
         wqkv = b["w_qkv"].float().cpu().numpy(); wgu = b["w_gate_up"].float().cpu().numpy()
@@ -451,29 +490,20 @@ def test_stack_full_size_two_blocks_against_oracle(B):
                                b["w_o"].float().cpu().numpy(), b["ffn_norm"].float().cpu().numpy(), wgu[:F], wgu[F:],
                                b["w_down"].float().cpu().numpy()))
     x = inp["x"].float().cpu().numpy()
-    ref = OS.stack_step(x, blocks, H, got["dec"], P_, V, k, 1, eps=cfg["eps"], theta=cfg["theta"],
-                        kept_override=got["kept"], assign_override=got["assign"])
-    # scores: the two sides' q, k differ by single bf16 steps (3e-2 relative is ~3x the floor seen at small sizes)
-    rel_s = (np.abs(got["S"] - ref["S"]) / np.abs(ref["S"])).max()
-    assert rel_s < 3e-2, rel_s
-    slot = np.full(V, -1, np.int32); slot[got["kept"]] = np.arange(k)
-    thr = np.sort(ref["S"])[::-1][k - 1]
-    diff = np.setxor1d(got["kept"], ref["own_kept_idx"])
-    assert all(abs(ref["S"][j] - thr) <= 3e-2 * thr for j in diff), "kept set differs away from the threshold"
-    # assignment on the oracle's own pre-merge states: different slots only where the cosines are within the band
-    wrong = np.nonzero(got["assign"] != ref["own_assign"])[0]
-    pm = ref["pre_merge"].astype(np.float32)
-    for m in wrong[:200]:
-        c = oracle.cosine(pm, P_ + int(m), P_ + int(got["kept"][got["assign"][m]]))
-        assert c >= ref["best_cos"][m] - 1e-2 * abs(ref["best_cos"][m]), (m, c, ref["best_cos"][m])
-    assert len(wrong) <= 0.02 * V, len(wrong)
+    kw = dict(kept=got["kept"], assign=got["assign"], eps=cfg["eps"], theta=cfg["theta"])
+    ref = stack_step_given(x, blocks, H, got["dec"], P_, V, k, 1, **kw)
+    alt = stack_step_given(x, blocks, H, got["dec"], P_, V, k, 1, store=jittered_bf16(3e-7, 1), **kw)
     np.testing.assert_array_equal(got["src_pos"], ref["src_pos"])
     y = got["y"].float().cpu().numpy().astype(np.float64)
-    rel = np.sqrt(np.mean((y - ref["y"]) ** 2)) / np.sqrt(np.mean(ref["y"] ** 2))
-    print(f"full-size two blocks: rel rms {rel:.2e}, max abs {np.abs(y - ref['y']).max():.2e}, score rel {rel_s:.2e}, "
-          f"kept diff {len(diff) // 2}, assign diff {len(wrong)}")
-    # floor of bf16 storage measured by the oracle on itself at small sizes: 5e-3 .. 7e-3 for 2 .. 4 blocks
-    assert rel < 2e-2, rel
+    rms = lambda a_, b_: np.sqrt(np.mean((a_ - b_) ** 2)) / np.sqrt(np.mean(b_ ** 2))
+    rel, floor = rms(y, ref["y"]), rms(alt["y"], ref["y"])
+    err, err_floor = np.abs(y - ref["y"]), np.abs(alt["y"] - ref["y"])
+    print(f"full-size two blocks: rel rms {rel:.2e} (floor {floor:.2e}), max abs {err.max():.2e} (floor {err_floor.max():.2e}), "
+          f"score rel {rel_s:.2e}, kept excused {n_kept}, assign excused {n_asg}")
+    assert rel <= 3.0 * floor + 1e-4, (rel, floor)                         # at the rounding floor the oracle measures on itself
+    assert err.max() <= 3.0 * err_floor.max() + 2.0 ** -8, (err.max(), err_floor.max())
+    excess = err - _whole_step_elementwise_bound(ref["y"], 2)
+    assert excess.max() <= 0, f"element-wise bound exceeded by {excess.max():.3e}"
 
 
 def test_stack_trajectory_with_decider_updates(B):
