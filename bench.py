@@ -6,9 +6,14 @@ d3tom_importance -> d3tom_select_topk -> d3tom_merge -> d3tom_attend (the attent
 pre-generated q/k/v of the merged length; the projection between merge and attention is not on the path).
 
 Prints ONE JSON line: denoise steps/s of the workload the metric is quoted on (the 3645-visual-token
-LaViDa-like sweep; the 1024-token LLaDA-V-like step is reported beside it under "also"), the roofline
-figure of the dominant kernel (HIP-event timings taken live, algorithmic bytes / flops from the shapes),
-and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+LaViDa-like sweep; the 1024-token LLaDA-V-like step and the batched serving shape are reported beside it
+under "also"), the roofline figure of the dominant kernel (HIP-event timings taken live, algorithmic bytes /
+flops from the shapes), and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+
+Which steps are timed.  The sweep has 32 steps of growing cost (deciders 2..64, keep ratio 0.10..0.50).  The K
+timed steps always cover it evenly: whole sweeps in order while K allows, and a remainder (or a K below 32)
+spread evenly over the sweep, so that the mean step time estimates the mean over the whole sweep whatever K
+is.  The indices are reported under "timed_steps".
 """
 from __future__ import annotations
 
@@ -90,7 +95,7 @@ class Runner:
         self.scale = 1.0 / float(np.sqrt(wl.dh))
 
     def step(self, i: int):
-        B, d = self.B, self.dev[i % len(self.dev)]
+        B, d = self.B, self.dev[i]
         lay = d["lay"]
         B.d3tom_importance(d["q"], d["k"], lay, self.scale, self.scores, self.ws_imp)
         B.d3tom_select_topk(self.scores, lay, self.kept, self.slot)
@@ -119,31 +124,43 @@ def algorithmic(wl, lay):
     return out
 
 
+def step_order(n: int, K: int):
+    """Indices of the K timed steps of an n-step workload: whole passes in order, the remainder spread evenly."""
+    full, rest = divmod(K, n)
+    order = list(range(n)) * full
+    order += [min(n - 1, int((i + 0.5) * n / rest)) for i in range(rest)]
+    return order
+
+
 def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
     from paper_2511_12280_amd import binding as B
     t0 = time.time()
     wl, dev = build_steps(wl_name)
     gen_s = time.time() - t0
     r = Runner(wl, dev)
-    for i in range(warmup):
+    n = len(dev)
+    order = step_order(n, steps)
+    for i in range(n):                   # untimed: every step once (first-use set-up, inputs touched)
+        r.step(i)
+    for i in step_order(n, warmup):
         r.step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
+    for i in order:
         r.step(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
     # the same K steps again with HIP events around every kernel launch
     B.d3tom_profile_enable(True)
-    for i in range(steps):
+    for i in order:
         r.step(i)
     torch.cuda.synchronize()
     prof = B.d3tom_profile_collect()
     B.d3tom_profile_enable(False)
     alg = {k: [0.0, 0.0] for k in prof}
-    for i in range(steps):
-        a = algorithmic(wl, dev[i % len(dev)]["lay"])
+    for i in order:
+        a = algorithmic(wl, dev[i]["lay"])
         for k in alg:
             by, fl = a.get(k, (0.0, 0.0))
             alg[k][0] += by; alg[k][1] += fl
@@ -164,11 +181,14 @@ def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
     for k in kernels:
         kernels[k]["share"] = round(prof[k][0] / tot_ms, 4)
     dom = max(kernels, key=lambda k: prof[k][0])
-    merge_us = sum(prof[k][0] for k in prof if k != "attend") * 1e3 / steps
-    attend_us = prof["attend"][0] * 1e3 / steps
+    # The event brackets add about 2 us per launch, so the bracketed times sum to more than the step takes
+    # un-bracketed.  The split of the step into merge layer and attention uses the bracketed SHARES applied to
+    # the un-bracketed step time: the two figures add up to ms_per_step.
+    us_per_step = elapsed * 1e6 / steps
+    attend_share = prof["attend"][0] / tot_ms
     res = dict(workload=wl_name, steps_per_s=steps / elapsed, ms_per_step=elapsed * 1e3 / steps,
-               merge_layer_us=round(merge_us, 2), attend_us=round(attend_us, 2), kernels=kernels, dominant=dom,
-               gen_s=round(gen_s, 1))
+               merge_layer_us=round(us_per_step * (1.0 - attend_share), 2), attend_us=round(us_per_step * attend_share, 2),
+               kernels=kernels, dominant=dom, gen_s=round(gen_s, 1), timed_steps=order)
     if cpu_baseline:
         res["cpu_baseline"] = oracle_baseline(wl, dev)
     return wl, res
@@ -197,19 +217,19 @@ def run_kv_cache(wl_name: str, steps: int, warmup: int):
     ko = torch.zeros((mx, wl.d), dtype=tdt, device="cuda"); vo = torch.zeros_like(ko)
     counts = torch.zeros(wl.V, dtype=torch.int32, device="cuda")
     ws = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_MERGE, 1, n, wl.V, wl.H, wl.dh, 1))
-    def step(i):
-        j = i % len(lays)
+    def step(j):
         B.d3tom_merge_kv(kc, vc, lays[j], kepts[j], B.D3TOM_MERGE_MEAN, ko, vo, None, counts, None, ws)
-    for i in range(warmup):
+    order = step_order(len(lays), steps)
+    for i in list(range(len(lays))) + step_order(len(lays), warmup):
         step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(steps):
+    for i in order:
         step(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     B.d3tom_profile_enable(True)
-    for i in range(steps):
+    for i in order:
         step(i)
     torch.cuda.synchronize()
     prof = B.d3tom_profile_collect()
@@ -331,7 +351,9 @@ def run_stack(traj_repeats: int = 1):
 
 def oracle_baseline(wl, dev):
     """The fp64 oracle, as it stands, on the host cores: whole steps of the workload (all five stages),
-    taken evenly over the sweep, until about 12 s of CPU time have been spent."""
+    taken in bit-reversed order (0, 16, 8, 24, ...) so that whatever number of steps fits into about 12 s of CPU
+    time is spread evenly over the sweep; every sampled step counts once, like every step of the sweep does in
+    the GPU figure, so the sample mean estimates the same sweep mean."""
     import oracle
     order = sorted(range(len(dev)), key=lambda i: (bin(i)[::-1], i))     # spread over the sweep, step 0 first
     done, spent, n_steps = [], 0.0, 0.0
@@ -348,21 +370,46 @@ def oracle_baseline(wl, dev):
         if spent >= 12.0:
             break
     return dict(value=round(n_steps / spent, 4), unit="steps/s", cores=oracle.threads(), kind="oracle",
-                sample=f"{len(done)} of {len(dev)} steps of the workload (indices {sorted(done)}), first sample of each, "
-                       f"all five stages, {spent:.1f} s of oracle time")
+                sample=f"{len(done)} of {len(dev)} steps of the workload, spread evenly over it (indices {sorted(done)}), "
+                       f"each weighted once, first sample of each, all five stages, {spent:.1f} s of oracle time")
 
 
-# HBM bytes per launch (fetch + write), averaged over the sweep, from the two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE) summarised in profiles/lavida_3645_sweep_hbm_traffic.txt; counters scaled by what
-# they read for a plain 256 MiB copy.  Counters cannot be read from inside this process, so the figures
-# are carried here and refreshed together with that profile.
-MEASURED_HBM_TRAFFIC = {
-    "lavida_3645_sweep": {
-        "imp_stats": 33.32e6, "imp_scores": 33.39e6, "imp_finish": 0.51e6, "topk_select": 0.05e6,
-        "merge_norms": 9.07e6, "cos_argmax": 98.49e6, "merge_assign": 0.27e6, "merge_scatter": 41.33e6,
-        "attend": 40.98e6,
-    },
-}
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "lavida_3645_sweep_hbm_traffic.txt")
+KERNEL_OF_SYMBOL = (("imp_stats", "imp_stats"), ("imp_scores", "imp_scores"), ("imp_finish", "imp_finish"), ("topk_select", "topk_select"),
+                    ("merge_norms", "merge_norms"), ("cos_argmax", "cos_argmax"), ("cos_reduce", "cos_reduce"),
+                    ("merge_scatter", "merge_scatter"), ("attend", "attend"))
+
+
+def measured_traffic(wl_name: str):
+    """HBM bytes per launch (fetch + write) of every kernel from the rocprofv3 --pmc summary kept under profiles/
+    (counters cannot be read from inside this process): {kernel: bytes}, launch-weighted over a kernel's template
+    variants, plus a note saying where the figures come from.  None when there is no summary for the workload."""
+    import re
+    if wl_name != "lavida_3645_sweep" or not os.path.exists(TRAFFIC_PROFILE):
+        return None, "no rocprofv3 counter summary for this workload under profiles/"
+    acc = {}
+    for line in open(TRAFFIC_PROFILE):
+        m = re.match(r"^(\S.*?)\s+(\d+)\s+([0-9.]+)\s+([0-9.]+)\s*$", line)
+        if not m:
+            continue
+        sym, launches, fetch, write = m.group(1), int(m.group(2)), float(m.group(3)), float(m.group(4))
+        for prefix, name in KERNEL_OF_SYMBOL:
+            if sym.startswith(prefix):
+                b, n = acc.get(name, (0.0, 0))
+                acc[name] = (b + (fetch + write) * 1e6 * launches, n + launches)
+    out = {k: b / n for k, (b, n) in acc.items() if n}
+    note = "from profiles/lavida_3645_sweep_hbm_traffic.txt (two rocprofv3 --pmc runs over whole sweeps), not measured in this run"
+    lib = os.path.join(ROOT, "paper_2511_12280_amd", "libd3tom.so")
+    if os.path.exists(lib) and os.path.getmtime(TRAFFIC_PROFILE) < os.path.getmtime(lib):
+        note += "; the summary is older than the library"
+    return out, note
+
+
+# The paper's own measurement at the sweep's first keep ratio, as context (another machine, a whole model on a
+# benchmark this build does not have): Table 2, D3ToM keeping 10 % of the visual tokens.
+PAPER_CONTEXT = {"source": "Table 2, D3ToM, 10 % of the visual tokens kept, LaViDa-LLaDA-8B on LLaVA-Bench, T = 32",
+                 "hardware": "NVIDIA A6000", "wall_clock_vs_unmerged": 0.426, "theoretical_flops_vs_unmerged": 0.302,
+                 "wall_clock_s": 492.70, "unmerged_wall_clock_s": 1156.65}
 
 
 def main():
@@ -371,7 +418,7 @@ def main():
     ap.add_argument("--steps", type=int, default=128)
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="lavida_3645_sweep")
-    ap.add_argument("--also", default="llada_v_1024", help="second workload reported beside the first ('' = none)")
+    ap.add_argument("--also", default="llada_v_1024,serving_b16", help="workloads reported beside the first ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stack", action="store_true", help="skip the full 32-block stack trajectory")
     ap.add_argument("--stack-only", action="store_true",
@@ -396,30 +443,42 @@ def main():
         return
     wl, res = run_workload(args.workload, args.steps, args.warmup, not args.no_cpu_baseline)
     dom = res["kernels"][res["dominant"]]
+    traffic, traffic_note = measured_traffic(wl.name)
     line = {
         "metric": "denoise steps/sec of the hot path (merge layer + bidirectional attention over the merged sequence)",
         "value": round(res["steps_per_s"], 2), "unit": "steps/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(res["ms_per_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.V} visual + {wl.P} prompt + {wl.O} response tokens, hidden {wl.d}, "
-                               f"{wl.H}x{wl.dh} heads, batch {wl.B}, {wl.note}", "timed": "inputs resident in HBM"},
+                               f"{wl.H}x{wl.dh} heads, batch {wl.B}, {wl.note}", "timed": "inputs resident in HBM",
+                   "timed_steps": res["timed_steps"]},
         "merge_layer_us": res["merge_layer_us"], "attend_us": res["attend_us"],
         "roofline": {"kernel": res["dominant"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
                      "unit": dom["unit"], "frac": dom["frac"],
-                     "traffic": MEASURED_HBM_TRAFFIC.get(wl.name, {}).get(res["dominant"]), "avg_us": dom["avg_us"]},
+                     "traffic": (traffic or {}).get(res["dominant"]), "traffic_source": traffic_note, "avg_us": dom["avg_us"]},
         "kernels": res["kernels"],
+        "paper_context": PAPER_CONTEXT,
     }
+    if traffic:
+        line["traffic_per_launch"] = {k: round(v) for k, v in traffic.items()}
     if "cpu_baseline" in res:
         line["cpu_baseline"] = res["cpu_baseline"]
-    if args.also:
-        _, r2 = run_workload(args.also, args.steps, args.warmup, False)
-        line["also"] = {args.also: {"steps_per_s": round(r2["steps_per_s"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
-                                    "merge_layer_us": r2["merge_layer_us"], "attend_us": r2["attend_us"],
-                                    "kernels": r2["kernels"]}}
-        if args.also == "llada_v_1024":
+    also = [a for a in args.also.split(",") if a]
+    if also:
+        line["also"] = {}
+    for name in also:
+        _, r2 = run_workload(name, args.steps, args.warmup, False)
+        d2 = r2["kernels"][r2["dominant"]]
+        line["also"][name] = {"steps_per_s": round(r2["steps_per_s"], 2), "ms_per_step": round(r2["ms_per_step"], 4),
+                              "merge_layer_us": r2["merge_layer_us"], "attend_us": r2["attend_us"],
+                              "roofline": {"kernel": r2["dominant"], "bound": d2["bound"], "achieved": d2["achieved"],
+                                           "peak": d2["peak"], "unit": d2["unit"], "frac": d2["frac"]},
+                              "kernels": r2["kernels"]}
+        if name == "llada_v_1024":
             # the workload text quotes 263 tokens after the merge, its own counts give 231 (timed above): both lengths
-            line["also"][args.also]["attend_alone_us"] = {str(n): round(time_attention(args.also, n, args.steps, args.warmup), 2)
-                                                          for n in (231, 263)}
+            line["also"][name]["attend_alone_us"] = {str(n): round(time_attention(name, n, args.steps, args.warmup), 2)
+                                                     for n in (231, 263)}
+    if also:
         line["also"]["kv_cache_of_" + args.workload] = run_kv_cache(args.workload, args.steps, args.warmup)
         if not args.no_stack:
             line["also"]["denoise_stack_3645"] = run_stack()

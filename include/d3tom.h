@@ -31,7 +31,11 @@
  * Workspace  `ws` is device scratch of at least d3tom_workspace_bytes(op, ...) bytes, 256-byte
  *            aligned.  It carries no state between calls; concurrent calls need separate ones.
  * Errors     The return value is a d3tom_status.  Arguments are validated on the host before
- *            anything is enqueued; on any status other than D3TOM_OK nothing was enqueued.
+ *            anything is enqueued: INVALID_ARG, NO_DECIDERS, WORKSPACE_TOO_SMALL and UNSUPPORTED mean
+ *            that nothing was enqueued.  D3TOM_ERR_DEVICE (the HIP runtime refused a launch or a
+ *            set-up call) can come from the middle of an entry point that enqueues several kernels:
+ *            earlier kernels of that call may then already be on the stream and the outputs are
+ *            unspecified.
  * Determinism  No floating-point atomics: the same inputs give bit-identical outputs.
  * NaN/Inf inputs are outside the contract.
  */
@@ -237,6 +241,25 @@ int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
 int d3tom_attend(const void* q, const void* k, const void* v, int dt,
                  int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
                  void* o, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * d3tom_attend_weighted — d3tom_attend with per-key weights taken from the merge's member counts
+ * (Section 3.2 aggregates by a plain sum; under MEAN aggregation a merged row stands for count_r
+ * original tokens but would enter the softmax of later layers once).  Key row j of sample b gets the
+ * weight w_j = counts[kept_off[b] + j - vis_start[b]] if it is one of the sample's merged rows
+ * (vis_start[b] <= j < vis_start[b] + kept_off[b+1] - kept_off[b], the layout d3tom_merge writes), else 1,
+ * and the attention probabilities are softmax_j(scale * q k_j + log w_j): exactly the attention over the
+ * sequence with row j written w_j times.  All weights 1 gives d3tom_attend.
+ *
+ *   counts, kept_off   as written by / passed to d3tom_merge (counts >= 1)
+ *   vis_start          int32[B]  first merged row of each sample (= first visual token)
+ *   other arguments as in d3tom_attend.  bf16 with dh 64 / 128 keeps a sample's log-weights in LDS:
+ *   max_seqlen above 3584 returns D3TOM_ERR_UNSUPPORTED there.
+ * ---------------------------------------------------------------------------------------- */
+int d3tom_attend_weighted(const void* q, const void* k, const void* v, int dt,
+                          int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
+                          const int32_t* counts, const int32_t* kept_off, const int32_t* vis_start,
+                          void* o, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
  * d3tom_update_deciders — the decider set for the next merge (Section 3.1, "The Decider-Guided

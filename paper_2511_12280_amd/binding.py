@@ -32,7 +32,7 @@ D3TOM_IMPORTANCE_STATIC_BYTES = 16 << 20
 D3TOM_LINEAR_PLAIN, D3TOM_LINEAR_RESIDUAL, D3TOM_LINEAR_SWIGLU = range(3)
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
-           "d3tom_status_string", "d3tom_importance", "d3tom_importance_static", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_update_deciders",
+           "d3tom_status_string", "d3tom_importance", "d3tom_importance_static", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_attend_weighted", "d3tom_update_deciders",
            "d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_linear_tile", "d3tom_stack_workspace_bytes", "d3tom_stack_step",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
@@ -64,6 +64,8 @@ _lib.d3tom_update_deciders.restype = _i
 _lib.d3tom_update_deciders.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp, _vp]
 _lib.d3tom_attend.restype = _i
 _lib.d3tom_attend.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _sz, _vp]
+_lib.d3tom_attend_weighted.restype = _i
+_lib.d3tom_attend_weighted.argtypes = [_vp, _vp, _vp, _i, _i, _vp, _i, _i, _i, _f, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_rmsnorm.restype = _i
 _lib.d3tom_rmsnorm.argtypes = [_vp, _vp, _i, _i, _f, _vp, _vp]
 _lib.d3tom_rope.restype = _i
@@ -281,6 +283,19 @@ def d3tom_attend(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: 
     _check(_lib.d3tom_attend(_ptr(q), _ptr(k), _ptr(v), _dt(q), B, _ptr(cu_seqlens), int(max_seqlen), H, dh,
                              float(scale), _ptr(o), _ptr(ws), ws.numel() if ws is not None else 0, _stream(stream)),
            "d3tom_attend")
+    return o
+
+
+def d3tom_attend_weighted(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int,
+                          scale: float, counts: torch.Tensor, kept_off: torch.Tensor, vis_start: torch.Tensor,
+                          o: torch.Tensor, stream=None) -> torch.Tensor:
+    """d3tom_attend with the merge's member counts as key weights (counts int32 [sum keep], kept_off int32 [B+1],
+    vis_start int32 [B], all on the device)."""
+    H, dh = q.shape[-2], q.shape[-1]
+    B = cu_seqlens.numel() - 1
+    _check(_lib.d3tom_attend_weighted(_ptr(q), _ptr(k), _ptr(v), _dt(q), B, _ptr(cu_seqlens), int(max_seqlen), H, dh,
+                                      float(scale), _ptr(counts), _ptr(kept_off), _ptr(vis_start), _ptr(o), None, 0,
+                                      _stream(stream)), "d3tom_attend_weighted")
     return o
 
 

@@ -82,10 +82,28 @@ __device__ __forceinline__ float att_pair_sum(float x) {
 }
 #endif
 
-template <int DH>
+// Size-weighted attention: key row j of sample b stands for w_j original tokens (the member counts of the
+// merge); its logit gets + log2(w_j) in the base-2 softmax, which is attention over the sequence with the row
+// written w_j times.  The weights are described the way the merge reports them: `counts` per kept slot; key
+// rows vis_start[b] .. vis_start[b] + (kept_off[b+1] - kept_off[b]) - 1 are the merged rows, every other row
+// weighs 1.
+struct KeyWeights {
+    const int32_t* counts;
+    const int32_t* kept_off;
+    const int32_t* vis_start;
+};
+__device__ __forceinline__ float key_log2_weight(const KeyWeights& kw, int b, int j) {
+    const int r = j - kw.vis_start[b];
+    const int k0 = kw.kept_off[b], kn = kw.kept_off[b + 1] - k0;
+    return (r >= 0 && r < kn) ? __log2f((float)max(kw.counts[k0 + r], 1)) : 0.f;
+}
+constexpr int ATT_WKEYS = 3584;     // longest sample of the weighted tiled kernel: its log2 weights sit in LDS, and two
+                                    // workgroups (64 KB ring + weights each) still fit the 160 KB of a CU
+
+template <int DH, bool WGT>
 __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o) {
+    const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o, KeyWeights kw) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int KS = DH / 16;                 // k-steps of the first product
     constexpr int DT = DH / 32;                 // 32-dim tiles of O^T
@@ -96,16 +114,21 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
     constexpr int TILE = ATT_BK * ROWB;         // bytes of one K (or V) tile
     constexpr int STAGE = 2 * TILE;
     extern __shared__ __attribute__((aligned(16))) char ring[];
+    __shared__ __attribute__((aligned(16))) float lw_s[WGT ? ATT_WKEYS + ATT_BK : 4];
 
     const int xcd = blockIdx.x & 7, li = blockIdx.x >> 3;
     const int hb = (li / nqt) * 8 + xcd, qt = li % nqt;         // hb = sample * H + head
     if (hb >= H * nB) return;
     const int h = hb % H, b = hb / H;
     const int tok0 = cu[b];
-    const int n = cu[b + 1] - tok0;
+    const int n = min(cu[b + 1] - tok0, WGT ? ATT_WKEYS : 0x7FFFFFFF);
     if (qt * ATT_BQ >= n) return;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if constexpr (WGT) {
+        for (int j = tid; j < ((n + ATT_BK - 1) / ATT_BK) * ATT_BK; j += 256) lw_s[j] = (j < n) ? key_log2_weight(kw, b, j) : 0.f;
+        __syncthreads();
+    }
     const int c = lane & 31, g = lane >> 5;
     const size_t rs = (size_t)H * DH;                      // token stride (elements)
     const uint16_t* kb = k + (size_t)tok0 * rs + (size_t)h * DH;
@@ -217,6 +240,47 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
         if (it + 1 < ntile) issue(key0 + ATT_BK, STG ^ 1);
         __builtin_amdgcn_sched_barrier(0);
         // online softmax in base 2 on the raw logits; element e of st[kt]: key kt*32 + (e/4)*8 + 4g + e%4, query c
+        if constexpr (WGT) {
+            // weighted: the maximum is taken on scale2 * logit + log2 w (m_run lives in that scaled domain)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int e4 = 0; e4 < 4; ++e4) {
+                    const f32x4 w4 = *reinterpret_cast<const f32x4*>(&lw_s[key0 + kt * 32 + e4 * 8 + g * 4]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const int key = key0 + kt * 32 + e4 * 8 + g * 4 + e;
+                        const float t = __builtin_fmaf(st[kt][e4 * 4 + e], scale2, w4[e]);
+                        st[kt][e4 * 4 + e] = (key < n) ? t : -INFINITY;
+                    }
+                }
+            float tmax = st[0][0];
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) tmax = fmaxf(tmax, st[kt][e]);
+            tmax = att_pair_max(tmax);
+            const float m_new = fmaxf(m_run, tmax);
+            float psum = 0.f;
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(st[kt][e] - m_new);
+                    st[kt][e] = p;
+                    psum += p;
+                }
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < DT; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
+            }
+            l_run += psum;
+            m_run = m_new;
+        } else {
         if (key0 + ATT_BK > n) {
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
@@ -253,6 +317,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_kernel(
         }
         l_run += psum;                               // per-lane partial; the two halves meet after the last tile
         m_run = m_new;
+        }
         __builtin_amdgcn_sched_barrier(0);
         read_v(1);
         __builtin_amdgcn_sched_barrier(0);
@@ -316,10 +381,10 @@ constexpr int ATS_MAX_KEYS = 512;
 template <int N>
 __device__ __forceinline__ void att_wait_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-template <int DH>
+template <int DH, bool WGT>
 __global__ __launch_bounds__(256, 2) void attend_bf16_short_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o) {
+    const int32_t* __restrict__ cu, int H, int nB, int nqt, float scale2, uint16_t* __restrict__ o, KeyWeights kw) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int KS = DH / 16;
     constexpr int DT = DH / 32;
@@ -332,16 +397,21 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_short_kernel(
     static_assert(WREG == DT * 16 * 64 * 4, "a wave's region also holds its partial O^T");
     extern __shared__ __attribute__((aligned(16))) char ring[];
     __shared__ float part_m[4][32], part_l[4][32];
+    __shared__ __attribute__((aligned(16))) float lw_s[WGT ? ATS_MAX_KEYS : 4];
 
     const int xcd = blockIdx.x & 7, li = blockIdx.x >> 3;
     const int hb = (li / nqt) * 8 + xcd, qt = li % nqt;
     if (hb >= H * nB) return;
     const int h = hb % H, b = hb / H;
     const int tok0 = cu[b];
-    const int n = cu[b + 1] - tok0;
+    const int n = min(cu[b + 1] - tok0, ATS_MAX_KEYS);
     if (qt * 32 >= n) return;
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if constexpr (WGT) {
+        for (int j = tid; j < ATS_MAX_KEYS; j += 256) lw_s[j] = (j < n) ? key_log2_weight(kw, b, j) : 0.f;
+        __syncthreads();
+    }
     const int c = lane & 31, g = lane >> 5;
     const size_t rs = (size_t)H * DH;
     const uint16_t* kb = k + (size_t)tok0 * rs + (size_t)h * DH;
@@ -423,36 +493,72 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_short_kernel(
         // the K fragments are in registers (the MFMAs above consumed them): the K tile is free
         if (more) issue_k(key0 + 4 * ATS_BK);
         __builtin_amdgcn_sched_barrier(0);
-        if (key0 + ATS_BK > n) {
+        if constexpr (WGT) {
+            // weighted: maximum and exponent on scale2 * logit + log2 w (m_run lives in that scaled domain)
+#pragma unroll
+            for (int e4 = 0; e4 < 4; ++e4) {
+                const f32x4 w4 = *reinterpret_cast<const f32x4*>(&lw_s[min(key0 + e4 * 8 + g * 4, ATS_MAX_KEYS - 4)]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int key = key0 + e4 * 8 + g * 4 + e;
+                    const float t = __builtin_fmaf(st[e4 * 4 + e], scale2, w4[e]);
+                    st[e4 * 4 + e] = (key < n) ? t : -INFINITY;
+                }
+            }
+            float tmax = st[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, st[e]);
+            tmax = att_pair_max(tmax);
+            const float m_new = fmaxf(m_run, tmax);
+            float psum = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const int key = key0 + (e >> 2) * 8 + g * 4 + (e & 3);
-                if (key >= n) st[e] = -INFINITY;
+                const float p = __builtin_amdgcn_exp2f(st[e] - m_new);
+                st[e] = p;
+                psum += p;
             }
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < DT; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
+            }
+            l_run += psum;
+            m_run = m_new;
+        } else {
+        if (key0 + ATS_BK > n) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int key = key0 + (e >> 2) * 8 + g * 4 + (e & 3);
+                    if (key >= n) st[e] = -INFINITY;
+                }
+            }
+            float tmax = st[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, st[e]);
+            tmax = att_pair_max(tmax);
+            const float m_new = fmaxf(m_run, tmax);                // finite: every tile holds >= 1 valid key
+            const float ms = m_new * scale2;
+            float psum = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale2, -ms));
+                st[e] = p;
+                psum += p;
+            }
+            if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
+                l_run *= alpha;
+#pragma unroll
+                for (int t = 0; t < DT; ++t)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
+            }
+            l_run += psum;
+            m_run = m_new;
         }
-        float tmax = st[0];
-#pragma unroll
-        for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, st[e]);
-        tmax = att_pair_max(tmax);
-        const float m_new = fmaxf(m_run, tmax);                // finite: every tile holds >= 1 valid key
-        const float ms = m_new * scale2;
-        float psum = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(st[e], scale2, -ms));
-            st[e] = p;
-            psum += p;
-        }
-        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * scale2);
-            l_run *= alpha;
-#pragma unroll
-            for (int t = 0; t < DT; ++t)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) ot[t][e] *= alpha;
-        }
-        l_run += psum;
-        m_run = m_new;
         __builtin_amdgcn_sched_barrier(0);
         // V of this tile: everything older than the K loads just issued has landed
         if (more) att_wait_loads<LD>(); else att_wait_loads<0>();
@@ -501,7 +607,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_short_kernel(
 #pragma unroll
     for (int w2 = 0; w2 < 4; ++w2) {
         const float mw = part_m[w2][c];
-        f[w2] = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mw - m) * scale2);
+        f[w2] = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f((mw - m) * (WGT ? 1.0f : scale2));
         l += part_l[w2][c] * f[w2];
     }
     const float inv = 1.0f / l;
@@ -529,7 +635,7 @@ __global__ __launch_bounds__(256, 2) void attend_bf16_short_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void attend_generic_kernel(
     const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, const int32_t* __restrict__ cu,
-    int H, int dh, float scale2, T* __restrict__ o) {
+    int H, int dh, float scale2, T* __restrict__ o, KeyWeights kw) {
     const int i = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = cu[b];
     const int n = cu[b + 1] - tok0;
@@ -550,6 +656,7 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(
             float s = 0.f;
             for (int cidx = 0; cidx < dh; ++cidx) s += qs[cidx] * Elem<T>::load(kr + cidx);
             s2 = s * scale2;
+            if (kw.counts) s2 += key_log2_weight(kw, b, j);
         }
         float wm = wave_max(s2);
         if (lane == 0) red[wave] = wm;
@@ -579,63 +686,82 @@ __global__ __launch_bounds__(256) void attend_generic_kernel(
 
 using namespace d3tom;
 
-extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
-                            int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
-                            void* o, void* ws, size_t ws_bytes, void* stream) {
-    (void)ws; (void)ws_bytes;
+static int attend_run(const void* q, const void* k, const void* v, int dt,
+                      int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
+                      const int32_t* counts, const int32_t* kept_off, const int32_t* vis_start, void* o, void* stream) {
     if (!q || !k || !v || !o || !cu_seqlens) return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || max_seqlen < 1 || H < 1 || dh < 1) return D3TOM_ERR_INVALID_ARG;
     if (!(scale > 0.f) || !(scale < 3.0e38f)) return D3TOM_ERR_INVALID_ARG;      // the running max is taken on raw logits
     if (dt != D3TOM_F32 && dt != D3TOM_BF16) return D3TOM_ERR_INVALID_ARG;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return D3TOM_ERR_INVALID_ARG;
     if (dh > 256 || (dt == D3TOM_BF16 ? (dh % 8) : (dh % 4))) return D3TOM_ERR_UNSUPPORTED;
+    const bool wgt = counts != nullptr;
+    const KeyWeights kw{counts, kept_off, vis_start};
     hipStream_t st = (hipStream_t)stream;
     const float scale2 = scale * LOG2E;
     // the tiled kernel addresses one sample's K / V rows with 32-bit byte offsets
     const bool fits32 = ((size_t)max_seqlen + ATT_BK) * (size_t)H * (size_t)dh * 2 < ((size_t)1 << 31);
+    const bool mfma = dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32;
+    // the weighted MFMA kernels keep a sample's log2 weights in LDS
+    if (wgt && mfma && max_seqlen > ATT_WKEYS) return D3TOM_ERR_UNSUPPORTED;
     // short samples and too few 128-query tiles to fill the chip: keys split across the waves (measured
     // crossover with the tiled kernel: ~550 keys at 32 heads)
-    if (dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32 && max_seqlen <= ATS_MAX_KEYS &&
-        (long)ceil_div(max_seqlen, ATT_BQ) * H * B <= 512) {
+    if (mfma && max_seqlen <= ATS_MAX_KEYS && (long)ceil_div(max_seqlen, ATT_BQ) * H * B <= 512) {
         const int nqt = ceil_div(max_seqlen, 32);
         const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)4 * 2 * ATS_BK * dh * 2;
         static PerDeviceOnce lds_setup_s;
         if (!lds_setup_s.run([] {
-                return raise_dynamic_lds(attend_bf16_short_kernel<128>, 4 * 2 * ATS_BK * 128 * 2) &&
-                       raise_dynamic_lds(attend_bf16_short_kernel<64>, 4 * 2 * ATS_BK * 64 * 2);
+                return raise_dynamic_lds(attend_bf16_short_kernel<128, false>, 4 * 2 * ATS_BK * 128 * 2) &&
+                       raise_dynamic_lds(attend_bf16_short_kernel<64, false>, 4 * 2 * ATS_BK * 64 * 2) &&
+                       raise_dynamic_lds(attend_bf16_short_kernel<128, true>, 4 * 2 * ATS_BK * 128 * 2) &&
+                       raise_dynamic_lds(attend_bf16_short_kernel<64, true>, 4 * 2 * ATS_BK * 64 * 2);
             }))
             return D3TOM_ERR_DEVICE;
-        if (dh == 128)
-            D3TOM_LAUNCH(ATTEND, st, attend_bf16_short_kernel<128><<<g, 256, lds, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
-        else
-            D3TOM_LAUNCH(ATTEND, st, attend_bf16_short_kernel<64><<<g, 256, lds, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
-    } else if (dt == D3TOM_BF16 && (dh == 128 || dh == 64) && fits32) {
+#define D3TOM_ATT(KERNEL)                                                                                            \
+    D3TOM_LAUNCH(ATTEND, st, (KERNEL<<<g, 256, lds, st>>>((const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, \
+                                                           cu_seqlens, H, B, nqt, scale2, (uint16_t*)o, kw)))
+        if (dh == 128) { if (wgt) D3TOM_ATT((attend_bf16_short_kernel<128, true>)); else D3TOM_ATT((attend_bf16_short_kernel<128, false>)); }
+        else           { if (wgt) D3TOM_ATT((attend_bf16_short_kernel<64, true>));  else D3TOM_ATT((attend_bf16_short_kernel<64, false>)); }
+    } else if (mfma) {
         const int nqt = ceil_div(max_seqlen, ATT_BQ);
         const dim3 g((unsigned)(8 * ceil_div(H * B, 8) * nqt));
         const size_t lds = (size_t)ATT_NS * 2 * ATT_BK * dh * 2;
         static PerDeviceOnce lds_setup;
         if (!lds_setup.run([] {
-                return raise_dynamic_lds(attend_bf16_kernel<128>, ATT_NS * 2 * ATT_BK * 128 * 2) &&
-                       raise_dynamic_lds(attend_bf16_kernel<64>, ATT_NS * 2 * ATT_BK * 64 * 2);
+                return raise_dynamic_lds(attend_bf16_kernel<128, false>, ATT_NS * 2 * ATT_BK * 128 * 2) &&
+                       raise_dynamic_lds(attend_bf16_kernel<64, false>, ATT_NS * 2 * ATT_BK * 64 * 2) &&
+                       raise_dynamic_lds(attend_bf16_kernel<128, true>, ATT_NS * 2 * ATT_BK * 128 * 2) &&
+                       raise_dynamic_lds(attend_bf16_kernel<64, true>, ATT_NS * 2 * ATT_BK * 64 * 2);
             }))
             return D3TOM_ERR_DEVICE;
-        if (dh == 128)
-            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<128><<<g, 256, lds, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
-        else
-            D3TOM_LAUNCH(ATTEND, st, attend_bf16_kernel<64><<<g, 256, lds, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, B, nqt, scale2, (uint16_t*)o));
+        if (dh == 128) { if (wgt) D3TOM_ATT((attend_bf16_kernel<128, true>)); else D3TOM_ATT((attend_bf16_kernel<128, false>)); }
+        else           { if (wgt) D3TOM_ATT((attend_bf16_kernel<64, true>));  else D3TOM_ATT((attend_bf16_kernel<64, false>)); }
+#undef D3TOM_ATT
     } else {
         const dim3 g(max_seqlen, H, B);
         if (dt == D3TOM_F32)
             D3TOM_LAUNCH(ATTEND, st, attend_generic_kernel<float><<<g, 256, 0, st>>>(
-                (const float*)q, (const float*)k, (const float*)v, cu_seqlens, H, dh, scale2, (float*)o));
+                (const float*)q, (const float*)k, (const float*)v, cu_seqlens, H, dh, scale2, (float*)o, kw));
         else
             D3TOM_LAUNCH(ATTEND, st, attend_generic_kernel<uint16_t><<<g, 256, 0, st>>>(
-                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, dh, scale2, (uint16_t*)o));
+                (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, cu_seqlens, H, dh, scale2, (uint16_t*)o, kw));
     }
     return D3TOM_OK;
+}
+
+extern "C" int d3tom_attend(const void* q, const void* k, const void* v, int dt,
+                            int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
+                            void* o, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    return attend_run(q, k, v, dt, B, cu_seqlens, max_seqlen, H, dh, scale, nullptr, nullptr, nullptr, o, stream);
+}
+
+extern "C" int d3tom_attend_weighted(const void* q, const void* k, const void* v, int dt,
+                                     int B, const int32_t* cu_seqlens, int max_seqlen, int H, int dh, float scale,
+                                     const int32_t* counts, const int32_t* kept_off, const int32_t* vis_start,
+                                     void* o, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    if (!counts || !kept_off || !vis_start) return D3TOM_ERR_INVALID_ARG;
+    return attend_run(q, k, v, dt, B, cu_seqlens, max_seqlen, H, dh, scale, counts, kept_off, vis_start, o, stream);
 }

@@ -3,7 +3,8 @@
 //
 // S_j = (1/H) sum_h sum_{i in D} softmax_j(scale * q_{i,h} . k_{j,h}), softmax over ALL keys of the
 // sample, written for the visual columns only.  The N x N matrix is never formed: only the |D|
-// decider rows are ever evaluated, in two sweeps over K:
+// decider rows are ever evaluated.  Large decider sets take two sweeps over K (below); small ones keep
+// the D x N x H logits of the first sweep and finish from those (imp_scores_from_logits):
 //
 //   sweep 1 (stats)   per (head, decider): running max and sum of exp2 over all keys, computed per
 //                     512-key chunk by one workgroup each and combined later in a fixed order
@@ -28,9 +29,10 @@ namespace d3tom {
 constexpr int IMP_KC_STATS = 512, IMP_SUB_STATS = IMP_KC_STATS / (4 * 16);
 constexpr int IMP_KC_SCORES = 512, IMP_SUB_SCORES = IMP_KC_SCORES / (4 * 16);
 
+constexpr int IMP_KEEP_MAXD_WS = 32;   // largest decider set whose logits are kept (workspace is sized for it)
 struct ImpWs {
-    size_t part_off, sp_off, cnt_off, c_off, total;
-    int NCH, NCHV, DPAD, VPAD;
+    size_t part_off, sp_off, cnt_off, c_off, logit_off, total;
+    int NCH, NCHV, DPAD, VPAD, NKB;
 };
 __host__ inline ImpWs imp_ws_layout(int B, int max_N, int max_V, int H, int max_D) {
     ImpWs w;
@@ -43,38 +45,46 @@ __host__ inline ImpWs imp_ws_layout(int B, int max_N, int max_V, int H, int max_
     w.sp_off = o;   o += align_up((size_t)B * H * w.VPAD * sizeof(float), 256);
     w.cnt_off = o;  o += align_up((size_t)B * w.NCHV * sizeof(int), 256);
     w.c_off = o;    o += align_up((size_t)B * H * max_D * sizeof(float), 256);   // generic path
+    w.NKB = w.NCH * (IMP_KC_STATS / 16);
+    w.logit_off = o;                                                              // kept logits (small decider sets)
+    if (max_D <= IMP_KEEP_MAXD_WS) o += align_up((size_t)B * w.NKB * H * w.DPAD * 16 * sizeof(float), 256);
     w.total = o;
     return w;
 }
 size_t importance_ws_bytes(int B, int max_N, int max_V, int H, int dh, int max_D) {
     (void)dh;
-    return imp_ws_layout(B, max_N, max_V, H, max_D).total;
+    // a workspace sized for a bound on the decider count must also serve every smaller count: small sets
+    // keep their logits, which can take more room than the statistics of a large set
+    const size_t a = imp_ws_layout(B, max_N, max_V, H, max_D).total;
+    const size_t b = imp_ws_layout(B, max_N, max_V, H, max_D < IMP_KEEP_MAXD_WS ? max_D : IMP_KEEP_MAXD_WS).total;
+    return a > b ? a : b;
 }
 
 // Load one MFMA operand row fragment: lane (r = lane % 16, g = lane / 16) takes elements
-// [g*DH/4 + kk*8, +8) of its row for k-step kk.
+// [kk*32 + g*8, +8) of its row for k-step kk, so the four lanes of a row fetch 64 contiguous bytes per
+// load instruction.
 template <int DH>
 __device__ __forceinline__ void load_frag(const uint16_t* row, int g, bool valid, bf16x8 (&f)[DH / 32]) {
-    const bf16x8* p = reinterpret_cast<const bf16x8*>(row + g * (DH / 4));
+    const bf16x8* p = reinterpret_cast<const bf16x8*>(row + g * 8);
 #pragma unroll
     for (int kk = 0; kk < DH / 32; ++kk) {
         bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-        f[kk] = valid ? p[kk] : z;
+        f[kk] = valid ? p[kk * 4] : z;
     }
 }
 
 constexpr int IMP_NB = 4;       // 16-decider blocks whose query fragments are fetched together
 
 // (running max, running sum of exp2) of decider rows over one IMP_KC_STATS-key chunk of one head
-template <int DH>
+template <int DH, bool KEEP>
 __global__ __launch_bounds__(256) void imp_stats_bf16(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
-    int max_D, int DPAD, int NCH, float2* __restrict__ part) {
+    int max_D, int DPAD, int NCH, float2* __restrict__ part, int NKB, float* __restrict__ logits) {
     constexpr int KS = DH / 32;
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
-    const int N = seq_off[b + 1] - tok0;
+    const int N = min(seq_off[b + 1] - tok0, NCH * IMP_KC_STATS);     // the workspace holds NCH chunks per head
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
     const int key_base = chunk * IMP_KC_STATS;
@@ -121,6 +131,13 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
                     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qf[nb][kk], kf[s][kk], acc, 0, 0, 0);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) l2[s][e] = kvalid[s] ? acc[e] * scale2 : -INFINITY;
+                if constexpr (KEEP) {
+                    // [key block][head][decider][key in block]: the 16 lanes of a decider row write 64 contiguous bytes
+                    const int kb = (key_base >> 4) + wave * IMP_SUB_STATS + s;
+                    float* lp = logits + (((size_t)(b * NKB + kb) * H + h) * DPAD + (db0 + nb) * 16 + 4 * g) * 16 + r;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) lp[e * 16] = l2[s][e];
+                }
             }
             // max over this wave's 64 keys first (in-lane, then the 16 key columns), then one exp2 per logit
 #pragma unroll
@@ -158,7 +175,7 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
     constexpr int KS = DH / 32;
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
-    const int N = seq_off[b + 1] - tok0;
+    const int N = min(seq_off[b + 1] - tok0, NCH * IMP_KC_STATS);
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
     const int vs = min(max(vis_start[b], 0), N);
@@ -235,6 +252,89 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
         v += __shfl_xor(v, 16, WAVE);
         v += __shfl_xor(v, 32, WAVE);
         if (g == 0) sp_row[key_base + (wave * IMP_SUB_SCORES + s) * 16 + r] = v;
+    }
+}
+
+// Small decider sets (at most IMP_KEEP_MAXD): the first sweep also writes its scaled logits, D x N x H
+// floats (a quarter of K's bytes at 16 deciders), in blocks of [16 keys' block][head][decider][16 keys], and
+// the scores come from those instead of a second sweep over K: one workgroup per 16-key block reads its
+// contiguous H x D x 64 bytes, subtracts each (head, decider) row's log-sum-exp and adds the exponentials
+// over deciders and heads, so the mean over heads is finished in the same pass (no per-head rows, no
+// third launch, K fetched once).
+constexpr int IMP_KEEP_MAXD = IMP_KEEP_MAXD_WS;
+__global__ __launch_bounds__(256) void imp_scores_from_logits(
+    int H, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_off,
+    const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count, const int32_t* __restrict__ score_off,
+    int max_D, int max_V, int DPAD, int NCH, int NKB, const float2* __restrict__ part, const float* __restrict__ logits,
+    float* __restrict__ scores) {
+    const int kb = blockIdx.x, b = blockIdx.y;
+    const int N = min(seq_off[b + 1] - seq_off[b], NCH * IMP_KC_STATS);
+    const int D = min(dec_off[b + 1] - dec_off[b], max_D);
+    const int vs = min(max(vis_start[b], 0), N);
+    const int V = min(min(vis_count[b], max_V), N - vs);
+    const int key0 = kb * 16;
+    if (D <= 0 || key0 >= vs + V || key0 + 16 <= vs || key0 >= N) return;
+    extern __shared__ float c_lds[];                    // [H][DPAD] log2-sum-exp2, +inf for padded decider rows
+    __shared__ float red[16][16];
+    constexpr int NBK = IMP_KEEP_MAXD / 16;             // 16-decider blocks a kept set can have
+    const int nblk = (D + 15) >> 4;                     // decider blocks the first sweep has written
+    // thread (key = t % 16, group = t / 16) takes decider row 16 ib + group of every head: the 256 threads
+    // read whole 1 KB blocks of logits.  All loads of up to 32 heads are requested before anything else, so
+    // their latency (the logits come from another XCD's writes, i.e. from memory) overlaps the statistics below.
+    const int key = threadIdx.x & 15, grp = threadIdx.x >> 4;
+    const float* lb = logits + ((size_t)(b * NKB + kb) * H) * DPAD * 16 + (size_t)grp * 16 + key;
+    float l[32][NBK];
+#pragma unroll
+    for (int h = 0; h < 32; ++h)
+#pragma unroll
+        for (int ib = 0; ib < NBK; ++ib)
+            l[h][ib] = (h < H && ib < nblk) ? lb[((size_t)h * DPAD + ib * 16) * 16] : -INFINITY;
+    const int nch = min((N + IMP_KC_STATS - 1) / IMP_KC_STATS, NCH);
+    for (int t = threadIdx.x; t < H * nblk * 16; t += 256) {
+        const int h = t / (nblk * 16), i = t - h * (nblk * 16);
+        float c = INFINITY;
+        if (i < D) {
+            const float2* p = part + ((size_t)(b * H + h) * NCH) * DPAD + i;
+            float m = -INFINITY, z = 0.f;
+            for (int c0 = 0; c0 < nch; c0 += 8) {           // 8 independent loads in flight, combined in chunk order
+                float2 a[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) a[u] = (c0 + u < nch) ? p[(size_t)(c0 + u) * DPAD] : make_float2(-INFINITY, 0.f);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) lse2_combine(m, z, a[u].x, a[u].y);
+            }
+            c = m + log2f(z);
+        }
+        c_lds[h * DPAD + i] = c;
+    }
+    __syncthreads();
+    float acc = 0.f;
+#pragma unroll
+    for (int h = 0; h < 32; ++h)
+#pragma unroll
+        for (int ib = 0; ib < NBK; ++ib)
+            if (h < H && ib < nblk) acc += __builtin_amdgcn_exp2f(l[h][ib] - c_lds[h * DPAD + ib * 16 + grp]);
+    for (int h0 = 32; h0 < H; h0 += 32) {               // more than 32 heads: the same, 32 heads at a time
+        float l2[32][NBK];
+#pragma unroll
+        for (int h = 0; h < 32; ++h)
+#pragma unroll
+            for (int ib = 0; ib < NBK; ++ib)
+                l2[h][ib] = (h0 + h < H && ib < nblk) ? lb[((size_t)(h0 + h) * DPAD + ib * 16) * 16] : -INFINITY;
+#pragma unroll
+        for (int h = 0; h < 32; ++h)
+#pragma unroll
+            for (int ib = 0; ib < NBK; ++ib)
+                if (h0 + h < H && ib < nblk) acc += __builtin_amdgcn_exp2f(l2[h][ib] - c_lds[(h0 + h) * DPAD + ib * 16 + grp]);
+    }
+    red[grp][key] = acc;
+    __syncthreads();
+    const int j = key0 + (int)threadIdx.x - vs;          // visual index of key threadIdx.x of this block
+    if (threadIdx.x < 16 && j >= 0 && j < V) {
+        float sum = 0.f;
+#pragma unroll
+        for (int gq = 0; gq < 16; ++gq) sum += red[gq][threadIdx.x];      // groups in ascending order
+        scores[score_off[b] + j] = sum / (float)H;
     }
 }
 
@@ -366,15 +466,30 @@ static int importance_run(const void* q, const void* k, int dt,
         const dim3 g1(w.NCH, H, B), g2(w.NCHV, H, B), g3(ceil_div(max_V, 256), B);
         const uint16_t* qq = (const uint16_t*)q;
         const uint16_t* kk = (const uint16_t*)k;
+        // small decider sets: the first sweep keeps its logits and the scores come from them (K fetched once)
+        const bool keep = max_D <= IMP_KEEP_MAXD;
+        float* logits = (float*)(wsb + w.logit_off);
+        if (keep) {
+            if (dh == 128)
+                D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<128, true><<<g1, 256, 0, st>>>(
+                    qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
+            else
+                D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<64, true><<<g1, 256, 0, st>>>(
+                    qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
+            const dim3 g2k(ceil_div(max_N, 16), B);
+            D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_from_logits<<<g2k, 256, (size_t)H * w.DPAD * sizeof(float), st>>>(
+                H, seq_off, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD, w.NCH, w.NKB, part, logits, scores));
+            return D3TOM_OK;
+        }
         if (dh == 128) {
-            D3TOM_LAUNCH(IMP_STATS, st, imp_stats_bf16<128><<<g1, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part));
+            D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<128, false><<<g1, 256, 0, st>>>(
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<128><<<g2, 256, 0, st>>>(
                 qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.VPAD,
                 part, sp));
         } else {
-            D3TOM_LAUNCH(IMP_STATS, st, imp_stats_bf16<64><<<g1, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part));
+            D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<64, false><<<g1, 256, 0, st>>>(
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<64><<<g2, 256, 0, st>>>(
                 qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.VPAD,
                 part, sp));

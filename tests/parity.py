@@ -109,6 +109,32 @@ def gpu_attend(qkv_list: Sequence[tuple], dtype: str, scale: Optional[float] = N
     return GpuStep.split(B.to_host(o), lens)
 
 
+def gpu_attend_weighted(qkv_list: Sequence[tuple], counts: Sequence[np.ndarray], vis_starts: Sequence[int], dtype: str,
+                        scale: Optional[float] = None) -> List[np.ndarray]:
+    """Variable-length batch through d3tom_attend_weighted: sample b's key rows vis_starts[b] .. + len(counts[b])
+    carry the member counts counts[b], every other row weighs 1."""
+    lens = [t[0].shape[0] for t in qkv_list]
+    H, dh = qkv_list[0][0].shape[1:]
+    q = B.to_device(np.concatenate([t[0] for t in qkv_list]), dtype)
+    k = B.to_device(np.concatenate([t[1] for t in qkv_list]), dtype)
+    v = B.to_device(np.concatenate([t[2] for t in qkv_list]), dtype)
+    o = torch.zeros_like(q)
+    i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    cu = i32(np.concatenate([[0], np.cumsum(lens)]))
+    kept_off = i32(np.concatenate([[0], np.cumsum([len(c) for c in counts])]))
+    B.d3tom_attend_weighted(q, k, v, cu, max(lens), (1.0 / np.sqrt(dh)) if scale is None else scale,
+                            i32(np.concatenate(counts)), kept_off, i32(vis_starts), o)
+    torch.cuda.synchronize()
+    return GpuStep.split(B.to_host(o), lens)
+
+
+def key_weights(n: int, vis_start: int, counts: np.ndarray) -> np.ndarray:
+    """Per-key weights of a merged sequence of n rows: the member counts on the merged rows, 1 elsewhere."""
+    w = np.ones(n, dtype=np.float64)
+    w[vis_start:vis_start + len(counts)] = counts
+    return w
+
+
 # ---- comparisons ------------------------------------------------------------------------------------
 def check_scores(S_gpu: np.ndarray, S_ref: np.ndarray):
     rel = np.abs(S_gpu.astype(np.float64) - S_ref) / np.maximum(np.abs(S_ref), 1e-300)
@@ -170,8 +196,8 @@ def check_merge(out: dict, x: np.ndarray, vis_start: int, V: int, kept: np.ndarr
     return float(err)
 
 
-def check_attend(o_gpu: np.ndarray, q, k, v, dtype: str, rows=None, scale=None):
-    ref = oracle.attend(q, k, v, scale=scale, rows=rows)
+def check_attend(o_gpu: np.ndarray, q, k, v, dtype: str, rows=None, scale=None, key_weight=None):
+    ref = oracle.attend(q, k, v, scale=scale, rows=rows, key_weight=key_weight)
     sel = slice(None) if rows is None else np.asarray(rows)
     err = np.abs(o_gpu.astype(np.float64)[sel] - ref[sel]).max()
     assert err <= TOL_O[dtype], f"attention max abs error {err:.3e}"

@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 if torch.cuda.is_available():
     from paper_2511_12280_amd import binding as B
     from parity import (GpuStep, check_assign, check_attend, check_full_sample, check_kept, check_merge,
-                        check_scores, gpu_attend)
+                        check_scores, gpu_attend, gpu_attend_weighted, key_weights)
 
 
 def _chain(samples, keeps, dtype, mode="mean", assign_rows=None, check=None):
@@ -176,6 +176,113 @@ def test_attend_special_cases_bf16():
     np.testing.assert_allclose(o1, o2, atol=2e-2)           # no mask: key order is irrelevant
 
 
+# ---- size-weighted attention (member counts of the merge as key weights) -------------------------------
+@pytest.mark.parametrize("H,dh,dtype,lens", [
+    (4, 128, "bf16", [700, 65, 1300]),          # tiled kernel, ragged
+    (3, 64, "bf16", [300, 1, 512, 33]),         # short-sample kernel
+    (2, 64, "f32", [90, 17]),                   # generic kernel, float32
+    (2, 40, "bf16", [70]),                      # generic kernel, odd head size
+])
+def test_attend_weighted_varlen(H, dh, dtype, lens):
+    rng = np.random.default_rng(len(lens) * 100 + dh)
+    qkv = [W.random_qkv(900 + n, n, H, dh, dtype) for n in lens]
+    vis, counts = [], []
+    for n in lens:
+        vs = int(rng.integers(0, max(1, n // 3)))
+        kn = int(rng.integers(0, n - vs + 1))          # merged rows: anything from none to the rest of the sample
+        vis.append(vs)
+        counts.append(rng.integers(1, 40, size=kn).astype(np.int32))
+    outs = gpu_attend_weighted(qkv, counts, vis, dtype)
+    plain = gpu_attend(qkv, dtype)
+    for (q, k, v), o, o1, vs, c, n in zip(qkv, outs, plain, vis, counts, lens):
+        check_attend(o, q, k, v, dtype, key_weight=key_weights(n, vs, c))
+        if len(c) and c.max() > 1 and n > 1:
+            assert np.abs(o - o1).max() > 1e-3          # the weights do change the result
+    # all counts 1: the plain attention, bit for bit (same kernel arithmetic up to the added zero)
+    ones = [np.ones(len(c), np.int32) for c in counts]
+    for o, o1 in zip(gpu_attend_weighted(qkv, ones, vis, dtype), plain):
+        np.testing.assert_allclose(o, o1, atol=TOL_SAME[dtype])
+
+
+TOL_SAME = {"bf16": 2.0 ** -7, "f32": 1e-5}
+
+
+def test_merge_counts_feed_weighted_attention():
+    """The counts d3tom_merge writes are what d3tom_attend_weighted reads: merge a sample, project the merged rows
+    (host, not on the path), attend with the counts as key weights, compare with the oracle given the same weights."""
+    wl = W.WORKLOADS["tiny_f32"]
+    g = W.SampleGen(wl)
+    s = g.step(16)
+    k = oracle.keep_count(wl.V, 0.25)
+    step, S, kept, mout, stats = _chain([s], [k], "f32")
+    q2, k2, v2 = g.proj.qkv(mout["y"][0])
+    n_m = q2.shape[0]
+    cu = torch.tensor([0, n_m], dtype=torch.int32, device="cuda")
+    o = torch.zeros((n_m,) + q2.shape[1:], dtype=torch.float32, device="cuda")
+    B.d3tom_attend_weighted(B.to_device(q2, "f32"), B.to_device(k2, "f32"), B.to_device(v2, "f32"), cu, n_m,
+                            1.0 / np.sqrt(q2.shape[2]), step.counts, step.lay.kept_off, step.lay.vis_start, o)
+    torch.cuda.synchronize()
+    assert mout["counts"][0].sum() == wl.V
+    check_attend(B.to_host(o), q2, k2, v2, "f32", key_weight=key_weights(n_m, s["vis_start"], mout["counts"][0]))
+
+
+# ---- degenerate inputs the oracle defines ------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,d,H", [("bf16", 512, 4), ("bf16", 4096, 32), ("f32", 96, 2)])
+def test_zero_rows_in_the_similarity_features(dtype, d, H):
+    """A zero row has cosine 0 with everything: a zero PRUNED row ties on all slots and goes to slot 0; a zero KEPT
+    row scores 0 against every pruned row, so it wins exactly the pruned rows whose other cosines are all negative.
+    MFMA path (bf16, d a multiple of 64, tiled and split along the contraction) and generic path (float32)."""
+    P, V, O = 6, 330, 10
+    c = W.random_case(71, P + V + O, d, H, P, V, 4, dtype=dtype, centres=3, noise=1.0)
+    x = c["x"].copy()
+    rng = np.random.default_rng(72)
+    kept = np.sort(rng.choice(V, size=9, replace=False)).astype(np.int32)
+    pruned = np.setdiff1d(np.arange(V), kept)
+    zero_pruned, zero_kept = pruned[[3, 100, 250]], kept[[0, 5]]
+    x[P + zero_pruned] = 0.0
+    x[P + zero_kept] = 0.0
+    # make a few pruned rows point away from every non-zero kept row, so that the zero kept rows get members
+    x[P + pruned[[7, 8]]] = -x[P + kept[2]]
+    c["x"] = x
+    step = GpuStep([c], [len(kept)], dtype)
+    out = step.merge([kept])
+    a = out["assign"][0]
+    ref, bc = oracle.assign(x, P, V, kept, return_cos=True)
+    assert np.all(a[zero_pruned] == 0) and np.all(ref[zero_pruned] == 0) and np.all(bc[zero_pruned] == 0.0)
+    check_assign(a, x, P, V, kept)
+    check_merge({key: out[key][0] for key in out}, x, P, V, kept, dtype)
+    assert np.isfinite(out["y"][0]).all()
+
+
+def test_deciders_anywhere_with_a_repeat_on_the_mfma_path():
+    """Decider positions inside and in front of the visual block, one of them listed twice (its row counts twice):
+    the score is defined for any list of rows."""
+    P, V, O, H, dh = 40, 600, 30, 4, 128
+    c = W.random_case(73, P + V + O, H * dh, H, P, V, 3, dtype="bf16", centres=50)
+    c["dec_idx"] = np.array([5, P + 10, P + V - 1, P + 10, P + V + 7, 0, 39], dtype=np.int32)
+    c["D"] = len(c["dec_idx"])
+    k = oracle.keep_count(V, 0.2)
+    step = GpuStep([c], [k], "bf16")
+    S = step.importance()
+    S_ref = oracle.importance(c["q"], c["k"], c["dec_idx"], P, V)
+    check_scores(S[0], S_ref)
+    kept, slot = step.select_topk()
+    check_kept(kept[0], slot[0], S_ref, k)
+    # and a long list (above the size whose logits are kept) with the same properties
+    c["dec_idx"] = np.concatenate([np.arange(P + 100, P + 140), np.arange(0, 8), [P + 100, P + 100]]).astype(np.int32)
+    c["D"] = len(c["dec_idx"])
+    step = GpuStep([c], [k], "bf16")
+    check_scores(step.importance()[0], oracle.importance(c["q"], c["k"], c["dec_idx"], P, V))
+
+
+def test_one_token_merged_away_at_full_width():
+    """keep_k = V - 1 at d = 4096: a single pruned row against V - 1 kept rows on the MFMA path."""
+    P, V, O, H, dh = 4, 300, 6, 32, 128
+    c = W.random_case(74, P + V + O, H * dh, H, P, V, 2, dtype="bf16", centres=20)
+    step, S, kept, mout, stats = _chain([c], [V - 1], "bf16")
+    assert mout["counts"][0].sum() == V and mout["counts"][0].max() == 2 and mout["y"][0].shape[0] == P + V - 1 + O
+
+
 # ---- full-size workloads ---------------------------------------------------------------------------------
 def test_llada_v_1024_full_chain():
     wl = W.WORKLOADS["llada_v_1024"]
@@ -193,7 +300,7 @@ def test_llada_v_1024_full_chain():
     check_attend(gpu_attend([qkv], "bf16")[0], *qkv, "bf16")
 
 
-@pytest.mark.parametrize("s_idx", [0, 31])
+@pytest.mark.parametrize("s_idx", [0, 5, 6, 16, 31])        # 5 | 6: the cosine tile height changes between them
 def test_lavida_3645_sweep_steps_sampled(s_idx):
     wl = W.WORKLOADS["lavida_3645_sweep"]
     g = W.SampleGen(wl)

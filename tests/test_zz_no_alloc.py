@@ -24,10 +24,11 @@ def _both(case):
     ws = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_IMPORTANCE, 1, lay.max_N, lay.max_V, H, dh, lay.max_D))
     B.d3tom_importance(q, k, lay, scale, ref, ws)
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated()
+    # torch's caching allocator counts every allocation request it serves: none may come from this call
+    before = torch.cuda.memory_stats().get("allocation.all.allocated", 0)
     B.d3tom_importance_static(q, k, lay, scale, out)
     torch.cuda.synchronize()
-    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.memory_stats().get("allocation.all.allocated", 0) == before
     return ref.cpu().numpy(), out.cpu().numpy()
 
 
