@@ -194,6 +194,41 @@ def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
     return wl, res
 
 
+def run_merge_layer_one_call(wl_name: str, steps: int, warmup: int):
+    """d3tom_merge_layer over the workload: the merge layer in one call with the kept counts computed on the
+    device from the keep ratios (tight host bounds on them, so the launch shapes are those of the separate calls)."""
+    from paper_2511_12280_amd import binding as B
+    wl, dev = build_steps(wl_name)
+    n = len(dev)
+    mx = lambda f: max(f(d["lay"]) for d in dev)
+    nb, mN, mV, mD = mx(lambda l: l.B), mx(lambda l: l.max_N), mx(lambda l: l.max_V), mx(lambda l: l.max_D)
+    i32 = lambda m: torch.zeros(m, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.float32, device="cuda")
+    keep_k, kept_off, out_off, kept_idx = i32(nb), i32(nb + 1), i32(nb + 1), i32(nb * mV)
+    y = torch.zeros((mx(lambda l: l.sum_N), wl.d), dtype=torch.bfloat16 if wl.dtype == "bf16" else torch.float32, device="cuda")
+    counts, src = i32(nb * mV), i32(mx(lambda l: l.sum_N))
+    ws = B.workspace(B.d3tom_merge_layer_workspace_bytes(nb, mN, mV, wl.H, wl.dh, mD))
+    ratios = []
+    for d in dev:
+        h = d["host"]
+        r = [h["sch"]["keep_ratio"]] if wl.B == 1 else [k / s["V"] for k, s in zip(h["keeps"], h["samples"])]
+        ratios.append(torch.tensor(r, dtype=torch.float64, device="cuda"))
+    scale = 1.0 / float(np.sqrt(wl.dh))
+    def step(i):
+        d = dev[i]; lay = d["lay"]
+        B.d3tom_merge_layer(d["q"], d["k"], d["x"], None, lay, scale, ratios[i], min(lay.keep), max(lay.keep),
+                            B.D3TOM_MERGE_MEAN, scores, keep_k, kept_off, kept_idx, out_off, y, None, counts, src, ws)
+    order = step_order(n, steps)
+    for i in list(range(n)) + step_order(n, warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in order:
+        step(i)
+    torch.cuda.synchronize()
+    return dict(merge_layer_us=round((time.perf_counter() - t0) * 1e6 / steps, 2), kept_counts="on the device, from the keep ratios")
+
+
 def run_kv_cache(wl_name: str, steps: int, warmup: int):
     """d3tom_merge_kv (Section 4.4) on a cache of the workload's prompt + visual rows: key cache = the
     synthetic hidden rows (they carry the cluster structure the routing sees), value cache = N(0,1) rows,
@@ -480,6 +515,7 @@ def main():
                                                      for n in (231, 263)}
     if also:
         line["also"]["kv_cache_of_" + args.workload] = run_kv_cache(args.workload, args.steps, args.warmup)
+        line["also"]["merge_layer_one_call_" + args.workload] = run_merge_layer_one_call(args.workload, args.steps, args.warmup)
         if not args.no_stack:
             line["also"]["denoise_stack_3645"] = run_stack()
     print(json.dumps(line))

@@ -224,6 +224,39 @@ int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
                    int32_t* src_pos, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * d3tom_merge_layer — the merge layer of one denoising step in one call (Algorithm 1, the block guarded by
+ * "l = l* and the decider set is not empty": S from the decider rows, TopK at the step's keep ratio, cosine
+ * assignment, aggregation, removal of the merged positions), i.e. d3tom_importance -> d3tom_select_topk ->
+ * d3tom_merge on one workspace, with the kept counts computed ON THE DEVICE from per-sample keep ratios
+ * (Section 3.2, "Timestep-Dependent Merge Schedule": the ratio may come from a schedule evaluated on the
+ * device), so that no host integer sits between the importance map and the merge.
+ *
+ *   keep_ratio  double[B] (device): keep ratio 1 - alpha_t of each sample; the kept count is
+ *               ceil(keep_ratio * |V_b| - 1e-9) clamped to [1, |V_b|], the arithmetic of d3tom_keep_count
+ *   min_keep, max_keep   host-known bounds on the kept counts (1 <= min_keep <= every count <= max_keep <=
+ *               max_V); they only size the launches: tight bounds give the launch shapes of the separate
+ *               calls, loose ones (1, max_V) are always valid
+ *   scores      float[vis_off[B]] out
+ *   keep_k      int32[B] out, kept_off int32[B+1] out, out_off int32[B+1] out: what the separate calls take as
+ *               inputs (counts, their prefix sums, first output row of each sample)
+ *   kept_idx    int32[B * max_keep or more] out, packed by kept_off
+ *   y           [sum of output rows, d] out; room for seq_off[B] rows is always enough
+ *   assign, counts, src_pos   optional outputs as in d3tom_merge
+ *   all other arguments as in d3tom_importance / d3tom_merge; vis_off = prefix sums of vis_count
+ * Workspace: d3tom_merge_layer_workspace_bytes.  Statuses as for the separate calls (an empty decider set
+ * returns D3TOM_ERR_NO_DECIDERS before anything is enqueued).
+ * ---------------------------------------------------------------------------------------- */
+size_t d3tom_merge_layer_workspace_bytes(int B, int max_N, int max_V, int H, int dh, int max_D);
+int d3tom_merge_layer(const void* q, const void* k, const void* x, const void* sim, int d, int d_sim, int dt,
+                      int B, const int32_t* seq_off, int H, int dh, float scale,
+                      const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
+                      const int32_t* vis_start, const int32_t* vis_count, const int32_t* vis_off,
+                      const double* keep_ratio, int max_N, int max_V, int min_keep, int max_keep, int mode,
+                      float* scores, int32_t* keep_k, int32_t* kept_off, int32_t* kept_idx, int32_t* out_off,
+                      void* y, int32_t* assign, int32_t* counts, int32_t* src_pos,
+                      void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * d3tom_attend — bidirectional attention over the shortened sequence (Section 3.2: the shortened
  * tensor propagates through the later layers; Section 4.3: the 2 n^2 d term of FLOPs_layer; the
  * model attends without a causal mask).

@@ -32,7 +32,7 @@ D3TOM_IMPORTANCE_STATIC_BYTES = 16 << 20
 D3TOM_LINEAR_PLAIN, D3TOM_LINEAR_RESIDUAL, D3TOM_LINEAR_SWIGLU = range(3)
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
-           "d3tom_status_string", "d3tom_importance", "d3tom_importance_static", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_attend", "d3tom_attend_weighted", "d3tom_update_deciders",
+           "d3tom_status_string", "d3tom_importance", "d3tom_importance_static", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_merge_layer_workspace_bytes", "d3tom_merge_layer", "d3tom_attend", "d3tom_attend_weighted", "d3tom_update_deciders",
            "d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_linear_tile", "d3tom_stack_workspace_bytes", "d3tom_stack_step",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
@@ -60,6 +60,11 @@ _lib.d3tom_merge.argtypes = [_vp, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, 
 _lib.d3tom_merge_kv.restype = _i
 _lib.d3tom_merge_kv.argtypes = [_vp, _vp, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i,
                                 _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.d3tom_merge_layer_workspace_bytes.restype = _sz
+_lib.d3tom_merge_layer_workspace_bytes.argtypes = [_i] * 6
+_lib.d3tom_merge_layer.restype = _i
+_lib.d3tom_merge_layer.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _vp, _i, _i, _f, _vp, _vp, _i, _i, _vp, _vp, _vp,
+                                   _vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.d3tom_update_deciders.restype = _i
 _lib.d3tom_update_deciders.argtypes = [_vp, _vp, _i, _i, _vp, _i, _vp, _vp, _vp, _vp]
 _lib.d3tom_attend.restype = _i
@@ -273,6 +278,30 @@ def d3tom_merge_kv(k_cache: torch.Tensor, v_cache: torch.Tensor, lay: Layout, ke
                                _ptr(src_pos), _ptr(ws), ws.numel(), _stream(stream)),
            "d3tom_merge_kv")
     return k_out, v_out
+
+
+def d3tom_merge_layer_workspace_bytes(B: int, max_N: int, max_V: int, H: int, dh: int, max_D: int) -> int:
+    return int(_lib.d3tom_merge_layer_workspace_bytes(B, max_N, max_V, H, dh, max_D))
+
+
+def d3tom_merge_layer(q: torch.Tensor, k: torch.Tensor, x: torch.Tensor, sim: Optional[torch.Tensor], lay: Layout, scale: float,
+                      keep_ratio: torch.Tensor, min_keep: int, max_keep: int, mode: int, scores: torch.Tensor,
+                      keep_k: torch.Tensor, kept_off: torch.Tensor, kept_idx: torch.Tensor, out_off: torch.Tensor,
+                      y: torch.Tensor, assign: Optional[torch.Tensor], counts: Optional[torch.Tensor],
+                      src_pos: Optional[torch.Tensor], ws: torch.Tensor, stream=None):
+    """The three merge-layer calls in one, kept counts from keep_ratio (float64 [B] on the device).  Only the sizes
+    and decider lists of `lay` are used; its keep counts are not."""
+    H, dh = q.shape[-2], q.shape[-1]
+    d = x.shape[-1]
+    d_sim = sim.shape[-1] if sim is not None else d
+    assert keep_ratio.dtype == torch.float64 and keep_ratio.numel() == lay.B
+    _check(_lib.d3tom_merge_layer(_ptr(q), _ptr(k), _ptr(x), _ptr(sim), d, d_sim, _dt(x), lay.B, _ptr(lay.seq_off), H, dh,
+                                  float(scale), _ptr(lay.dec_idx), _ptr(lay.dec_off), lay.min_D, lay.max_D,
+                                  _ptr(lay.vis_start), _ptr(lay.vis_count), _ptr(lay.vis_off), _ptr(keep_ratio),
+                                  lay.max_N, lay.max_V, int(min_keep), int(max_keep), int(mode), _ptr(scores), _ptr(keep_k),
+                                  _ptr(kept_off), _ptr(kept_idx), _ptr(out_off), _ptr(y), _ptr(assign), _ptr(counts),
+                                  _ptr(src_pos), _ptr(ws), ws.numel(), _stream(stream)), "d3tom_merge_layer")
+    return y
 
 
 def d3tom_attend(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, cu_seqlens: torch.Tensor, max_seqlen: int,

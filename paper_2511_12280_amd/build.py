@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libd3tom.so")
 SOURCES = ["api.hip", "importance.hip", "topk.hip", "merge.hip", "attend.hip", "deciders.hip", "linear.hip", "block_ops.hip",
-           "stack.hip"]
+           "stack.hip", "pipeline.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # no packed-fp32 VALU forms
          "-Wall", "-Wno-unused-function"]

@@ -20,7 +20,7 @@
 //
 // The generic path (any float type / head size) is a plain one-thread-per-output kernel pair.
 #include <mutex>
-#include "common.hpp"
+#include "internal.hpp"
 
 namespace d3tom {
 
@@ -431,8 +431,8 @@ __global__ __launch_bounds__(256) void imp_scores_generic(
 
 using namespace d3tom;
 
-// Host-side argument checks shared by the two entry points (everything except the workspace).
-static int importance_check(const void* q, const void* k, int dt, int B, const int32_t* seq_off, int H, int dh, float scale,
+// Host-side argument checks shared by the entry points (everything except the workspace).
+int d3tom::importance_check(const void* q, const void* k, int dt, int B, const int32_t* seq_off, int H, int dh, float scale,
                             const int32_t* dec_idx, const int32_t* dec_off, int min_D, int max_D,
                             const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,
                             int max_N, int max_V, const float* scores) {
@@ -450,7 +450,7 @@ static int importance_check(const void* q, const void* k, int dt, int B, const i
 }
 
 // The launches; arguments and workspace have been checked.
-static int importance_run(const void* q, const void* k, int dt,
+int d3tom::importance_run(const void* q, const void* k, int dt,
                           int B, const int32_t* seq_off, int H, int dh, float scale,
                           const int32_t* dec_idx, const int32_t* dec_off, int max_D,
                           const int32_t* vis_start, const int32_t* vis_count, const int32_t* score_off,

@@ -17,7 +17,7 @@
 //             other rows are copied; one store per element, no float atomics
 //
 // All similarities are taken on the rows as given (assignment first, aggregation afterwards).
-#include "common.hpp"
+#include "internal.hpp"
 #include "direct_load.hpp"
 
 namespace d3tom {
@@ -666,7 +666,7 @@ using namespace d3tom;
 
 // Both entry points: norms + pruned list, cosine argmax, token -> slot table, scatter of one or two
 // payloads that share the routing.
-static int merge_run(const void* x0, void* y0, const void* x1, void* y1, const void* sim, int d, int d_sim, int dt,
+int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const void* sim, int d, int d_sim, int dt,
                      int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
                      const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
                      int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,

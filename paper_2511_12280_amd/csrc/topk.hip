@@ -9,7 +9,7 @@
 // (score descending, index ascending).  Integer LDS atomics only: deterministic.  Scores of one sample
 // share their sign and exponent bits, so the leading digits land in one or two bins; per-wave
 // histograms keep those same-address updates from serialising across the whole workgroup.
-#include "common.hpp"
+#include "internal.hpp"
 
 namespace d3tom {
 
@@ -42,20 +42,54 @@ __device__ __forceinline__ int block_excl_scan(int v, int* wsum /*[17]*/, int* t
     return wsum[wave] + inc - v;
 }
 
+// Kept count at a keep ratio (Section 3.2: rank at most (1 - alpha)|V|; a fractional product is rounded up):
+// ceil(ratio * V - 1e-9) clamped to [1, V], in double with separately rounded product and difference, i.e.
+// the same arithmetic as the host helper d3tom_keep_count.
+__device__ __forceinline__ int keep_count_device(int V, double ratio) {
+    double c = ceil(__dsub_rn(__dmul_rn(ratio, (double)V), 1e-9));
+    if (!(c >= 1.0)) c = 1.0;
+    if (c > (double)V) c = (double)V;
+    return (int)c;
+}
+
 __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ score_off, const int32_t* __restrict__ keep_k,
-    const int32_t* __restrict__ kept_off, int max_V, int32_t* __restrict__ kept_idx, int32_t* __restrict__ slot_of) {
+    const int32_t* __restrict__ kept_off, int max_V, int32_t* __restrict__ kept_idx, int32_t* __restrict__ slot_of,
+    const double* __restrict__ keep_ratio, const int32_t* __restrict__ seq_off, int32_t* __restrict__ keep_k_out,
+    int32_t* __restrict__ kept_off_out, int32_t* __restrict__ out_off_out) {
     extern __shared__ uint32_t ukey[];                 // [max_V]
     __shared__ int whist[16][256];        // one digit histogram per wave: same-bin updates only collide inside a wave
     __shared__ int wsum[17];
     __shared__ int sel[3];
     __shared__ uint32_t wrange[32];
+    __shared__ int plan[2];               // kept count of this sample, first slot of this sample in kept_idx
     const int b = blockIdx.x;
     const int s0 = score_off[b];
     const int V = min(score_off[b + 1] - s0, max_V);
-    if (V <= 0) return;
-    const int kk = min(max(keep_k[b], 1), V);
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    if (keep_ratio) {
+        // kept counts from the ratios, on the device: this sample's count and the prefix sums over the samples
+        // in front of it (every workgroup repeats the short loop; the last one also writes the totals)
+        if (tid == 0) {
+            int koff = 0, ooff = 0, kb = 1;
+            for (int bb = 0; bb <= b; ++bb) {
+                const int Vb = min(score_off[bb + 1] - score_off[bb], max_V);
+                const int kcur = Vb > 0 ? keep_count_device(Vb, keep_ratio[bb]) : 0;
+                if (bb == b) { kb = kcur; break; }
+                koff += kcur;
+                ooff += (seq_off[bb + 1] - seq_off[bb]) - (Vb - kcur);
+            }
+            plan[0] = kb; plan[1] = koff;
+            keep_k_out[b] = kb; kept_off_out[b] = koff; out_off_out[b] = ooff;
+            if (b == (int)gridDim.x - 1) {
+                kept_off_out[b + 1] = koff + kb;
+                out_off_out[b + 1] = ooff + (seq_off[b + 1] - seq_off[b]) - (V - kb);
+            }
+        }
+        __syncthreads();
+    }
+    if (V <= 0) return;
+    const int kk = keep_ratio ? plan[0] : min(max(keep_k[b], 1), V);
 
     // keys, and the range they span: bits above the highest differing bit are common to all keys
     uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
@@ -152,7 +186,7 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
     }
     int tot_keep;
     int slot = block_excl_scan(n_keep, wsum, &tot_keep);
-    const int k0 = kept_off[b];
+    const int k0 = keep_ratio ? plan[1] : kept_off[b];
     int e = eq_before;
     for (int j = j0; j < j1; ++j) {
         const uint32_t u = ukey[j];
@@ -167,18 +201,26 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
 
 using namespace d3tom;
 
-extern "C" int d3tom_select_topk(const float* scores, int B, const int32_t* score_off, const int32_t* keep_k,
-                                 const int32_t* kept_off, int max_V,
-                                 int32_t* kept_idx, int32_t* slot_of,
-                                 void* ws, size_t ws_bytes, void* stream) {
-    (void)ws; (void)ws_bytes;
-    if (!scores || !score_off || !keep_k || !kept_off || !kept_idx || !slot_of) return D3TOM_ERR_INVALID_ARG;
+int d3tom::topk_run(const float* scores, int B, const int32_t* score_off, const int32_t* keep_k, const int32_t* kept_off,
+                    int max_V, int32_t* kept_idx, int32_t* slot_of, const double* keep_ratio, const int32_t* seq_off,
+                    int32_t* keep_k_out, int32_t* kept_off_out, int32_t* out_off_out, void* stream) {
+    if (!scores || !score_off || !kept_idx || !slot_of) return D3TOM_ERR_INVALID_ARG;
+    if (keep_ratio ? (!seq_off || !keep_k_out || !kept_off_out || !out_off_out) : (!keep_k || !kept_off)) return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || max_V < 1) return D3TOM_ERR_INVALID_ARG;
     if (max_V > D3TOM_MAX_VISUAL) return D3TOM_ERR_UNSUPPORTED;
     static PerDeviceOnce lds_setup;
     if (!lds_setup.run([] { return raise_dynamic_lds(topk_select_kernel, D3TOM_MAX_VISUAL * 4); })) return D3TOM_ERR_DEVICE;
     hipStream_t st = (hipStream_t)stream;
     D3TOM_LAUNCH(TOPK_SELECT, st, topk_select_kernel<<<B, TOPK_THREADS, (size_t)max_V * 4, st>>>(
-        scores, score_off, keep_k, kept_off, max_V, kept_idx, slot_of));
+        scores, score_off, keep_k, kept_off, max_V, kept_idx, slot_of, keep_ratio, seq_off, keep_k_out, kept_off_out, out_off_out));
     return D3TOM_OK;
+}
+
+extern "C" int d3tom_select_topk(const float* scores, int B, const int32_t* score_off, const int32_t* keep_k,
+                                 const int32_t* kept_off, int max_V,
+                                 int32_t* kept_idx, int32_t* slot_of,
+                                 void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    return topk_run(scores, B, score_off, keep_k, kept_off, max_V, kept_idx, slot_of, nullptr, nullptr, nullptr, nullptr,
+                    nullptr, stream);
 }

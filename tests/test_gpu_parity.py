@@ -226,6 +226,53 @@ def test_merge_counts_feed_weighted_attention():
     check_attend(B.to_host(o), q2, k2, v2, "f32", key_weight=key_weights(n_m, s["vis_start"], mout["counts"][0]))
 
 
+# ---- the merge layer in one call, kept counts computed on the device --------------------------------------
+@pytest.mark.parametrize("tight", [True, False])
+def test_merge_layer_one_call_with_device_side_keep_counts(tight):
+    """d3tom_merge_layer against the three separate calls on a ragged batch: the kept counts it computes on the
+    device from the ratios are those of d3tom_keep_count (and of the oracle), and with tight bounds on them every
+    output is bit-identical to the separate calls; with the loosest bounds (1 .. |V|) the launches are shaped
+    differently, so the outputs are checked against the oracle instead."""
+    shapes = [(20, 300, 30, 9, 0.2), (64, 513, 64, 33, 0.5), (1, 128, 5, 1, 0.1), (7, 129, 300, 20, 1.0 / 3.0), (0, 64, 2, 2, 1.0),
+              (3, 700, 9, 4, 0.25)]
+    samples, ratios = [], []
+    for i, (P, V, O, D, keep) in enumerate(shapes):
+        samples.append(W.random_case(300 + i, P + V + O, 4 * 128, 4, P, V, D, dtype="bf16", centres=max(3, V // 5)))
+        ratios.append(keep)
+    keeps = [oracle.keep_count(s["V"], r) for s, r in zip(samples, ratios)]
+    assert keeps == [B.d3tom_keep_count(s["V"], r) for s, r in zip(samples, ratios)]
+    ref = GpuStep(samples, keeps, "bf16")
+    S = ref.importance(); kept, slot = ref.select_topk(); mout = ref.merge()
+    lay = ref.lay
+    nb = lay.B
+    dev_i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
+    scores = torch.zeros(lay.sum_V, dtype=torch.float32, device="cuda")
+    keep_k, kept_off, out_off = dev_i32(nb), dev_i32(nb + 1), dev_i32(nb + 1)
+    kept_idx = dev_i32(nb * lay.max_V)
+    y = torch.zeros((lay.sum_N, ref.d), dtype=torch.bfloat16, device="cuda")
+    assign, counts, src_pos = dev_i32(lay.sum_V), dev_i32(nb * lay.max_V), dev_i32(lay.sum_N)
+    ws = B.workspace(B.d3tom_merge_layer_workspace_bytes(nb, lay.max_N, lay.max_V, ref.H, ref.dh, lay.max_D))
+    ws.fill_(255)
+    lo, hi = (min(keeps), max(keeps)) if tight else (1, lay.max_V)
+    B.d3tom_merge_layer(ref.q, ref.k, ref.x, None, lay, ref.scale, torch.tensor(ratios, dtype=torch.float64, device="cuda"),
+                        lo, hi, B.D3TOM_MERGE_MEAN, scores, keep_k, kept_off, kept_idx, out_off, y, assign, counts, src_pos, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(keep_k.cpu().numpy(), keeps)
+    np.testing.assert_array_equal(kept_off.cpu().numpy(), np.concatenate([[0], np.cumsum(keeps)]))
+    np.testing.assert_array_equal(out_off.cpu().numpy(), np.concatenate([[0], np.cumsum(lay.Nm)]))
+    np.testing.assert_array_equal(scores.cpu().numpy(), np.concatenate(S))
+    np.testing.assert_array_equal(kept_idx[:lay.sum_keep].cpu().numpy(), np.concatenate(kept))
+    got = dict(y=GpuStep.split(B.to_host(y[:lay.sum_Nm]), lay.Nm), assign=GpuStep.split(assign.cpu().numpy(), lay.V),
+               counts=GpuStep.split(counts[:lay.sum_keep].cpu().numpy(), lay.keep),
+               src_pos=GpuStep.split(src_pos[:lay.sum_Nm].cpu().numpy(), lay.Nm))
+    for b in range(nb):
+        if tight:
+            for key in got:
+                np.testing.assert_array_equal(got[key][b], mout[key][b])
+        else:
+            check_full_sample(ref, b, S, kept, slot, got)
+
+
 # ---- degenerate inputs the oracle defines ------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,d,H", [("bf16", 512, 4), ("bf16", 4096, 32), ("f32", 96, 2)])
 def test_zero_rows_in_the_similarity_features(dtype, d, H):
