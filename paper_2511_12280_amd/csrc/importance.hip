@@ -25,18 +25,21 @@
 namespace d3tom {
 
 // keys per workgroup (4 waves x SUB sub-tiles x 16): every workgroup re-fetches the decider rows of its
-// head, so few large chunks (one workgroup per CU at 3.7k tokens x 32 heads) beat many small ones
-constexpr int IMP_KC_STATS = 512, IMP_SUB_STATS = IMP_KC_STATS / (4 * 16);
+// head, so few large chunks (one workgroup per CU at 3.7k tokens x 32 heads) beat many small ones; when
+// 512-key chunks would leave CUs idle (short sequences) the first sweep takes 256-key chunks instead
+// (8.5 instead of 11.5 us at 1152 tokens)
+constexpr int IMP_KC_STATS = 512;
 constexpr int IMP_KC_SCORES = 512, IMP_SUB_SCORES = IMP_KC_SCORES / (4 * 16);
 
 constexpr int IMP_KEEP_MAXD_WS = 32;   // largest decider set whose logits are kept (workspace is sized for it)
 struct ImpWs {
     size_t part_off, sp_off, cnt_off, c_off, logit_off, total;
-    int NCH, NCHV, DPAD, VPAD, NKB;
+    int KC, NCH, NCHV, DPAD, VPAD, NKB;
 };
 __host__ inline ImpWs imp_ws_layout(int B, int max_N, int max_V, int H, int max_D) {
     ImpWs w;
-    w.NCH = ceil_div(max_N, IMP_KC_STATS);
+    w.KC = ((long)ceil_div(max_N, IMP_KC_STATS) * H * B < 256) ? IMP_KC_STATS / 2 : IMP_KC_STATS;     // keys per chunk of the first sweep
+    w.NCH = ceil_div(max_N, w.KC);
     w.NCHV = ceil_div(max_V, IMP_KC_SCORES);
     w.DPAD = ceil_div(max_D, 16) * 16;
     w.VPAD = w.NCHV * IMP_KC_SCORES;
@@ -45,7 +48,7 @@ __host__ inline ImpWs imp_ws_layout(int B, int max_N, int max_V, int H, int max_
     w.sp_off = o;   o += align_up((size_t)B * H * w.VPAD * sizeof(float), 256);
     w.cnt_off = o;  o += align_up((size_t)B * w.NCHV * sizeof(int), 256);
     w.c_off = o;    o += align_up((size_t)B * H * max_D * sizeof(float), 256);   // generic path
-    w.NKB = w.NCH * (IMP_KC_STATS / 16);
+    w.NKB = w.NCH * (w.KC / 16);
     w.logit_off = o;                                                              // kept logits (small decider sets)
     if (max_D <= IMP_KEEP_MAXD_WS) o += align_up((size_t)B * w.NKB * H * w.DPAD * 16 * sizeof(float), 256);
     w.total = o;
@@ -75,8 +78,8 @@ __device__ __forceinline__ void load_frag(const uint16_t* row, int g, bool valid
 
 constexpr int IMP_NB = 4;       // 16-decider blocks whose query fragments are fetched together
 
-// (running max, running sum of exp2) of decider rows over one IMP_KC_STATS-key chunk of one head
-template <int DH, bool KEEP>
+// (running max, running sum of exp2) of decider rows over one chunk of IMP_SUB_STATS x 64 keys of one head
+template <int DH, bool KEEP, int IMP_SUB_STATS>
 __global__ __launch_bounds__(256) void imp_stats_bf16(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
@@ -84,10 +87,11 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
     constexpr int KS = DH / 32;
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
-    const int N = min(seq_off[b + 1] - tok0, NCH * IMP_KC_STATS);     // the workspace holds NCH chunks per head
+    constexpr int KC = IMP_SUB_STATS * 64;
+    const int N = min(seq_off[b + 1] - tok0, NCH * KC);               // the workspace holds NCH chunks per head
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
-    const int key_base = chunk * IMP_KC_STATS;
+    const int key_base = chunk * KC;
     if (key_base >= N || D <= 0) return;
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r = lane & 15, g = lane >> 4;
@@ -171,11 +175,11 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, int H, float scale2,
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
     const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
-    int max_D, int max_V, int DPAD, int NCH, int VPAD, const float2* __restrict__ part, float* __restrict__ sp) {
+    int max_D, int max_V, int DPAD, int NCH, int KC, int VPAD, const float2* __restrict__ part, float* __restrict__ sp) {
     constexpr int KS = DH / 32;
     const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
-    const int N = min(seq_off[b + 1] - tok0, NCH * IMP_KC_STATS);
+    const int N = min(seq_off[b + 1] - tok0, NCH * KC);
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int32_t* dec = dec_idx + dec_off[b];
     const int vs = min(max(vis_start[b], 0), N);
@@ -190,7 +194,7 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
 #pragma unroll
     for (int nb = 0; nb < IMP_NB; ++nb) pos0[nb] = (nb * 16 + r < D) ? dec[nb * 16 + r] : 0;
     // log2-sum-exp2 of every decider row of this head, key chunks combined in ascending order
-    const int nch = (N + IMP_KC_STATS - 1) / IMP_KC_STATS;
+    const int nch = (N + KC - 1) / KC;
     for (int t = threadIdx.x; t < D; t += 256) {
         const float2* p = part + ((size_t)(b * H + h) * NCH) * DPAD + t;
         float m = -INFINITY, z = 0.f;
@@ -265,10 +269,10 @@ constexpr int IMP_KEEP_MAXD = IMP_KEEP_MAXD_WS;
 __global__ __launch_bounds__(256) void imp_scores_from_logits(
     int H, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_off,
     const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count, const int32_t* __restrict__ score_off,
-    int max_D, int max_V, int DPAD, int NCH, int NKB, const float2* __restrict__ part, const float* __restrict__ logits,
+    int max_D, int max_V, int DPAD, int NCH, int KC, int NKB, const float2* __restrict__ part, const float* __restrict__ logits,
     float* __restrict__ scores) {
     const int kb = blockIdx.x, b = blockIdx.y;
-    const int N = min(seq_off[b + 1] - seq_off[b], NCH * IMP_KC_STATS);
+    const int N = min(seq_off[b + 1] - seq_off[b], NCH * KC);
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
     const int vs = min(max(vis_start[b], 0), N);
     const int V = min(min(vis_count[b], max_V), N - vs);
@@ -289,7 +293,7 @@ __global__ __launch_bounds__(256) void imp_scores_from_logits(
 #pragma unroll
         for (int ib = 0; ib < NBK; ++ib)
             l[h][ib] = (h < H && ib < nblk) ? lb[((size_t)h * DPAD + ib * 16) * 16] : -INFINITY;
-    const int nch = min((N + IMP_KC_STATS - 1) / IMP_KC_STATS, NCH);
+    const int nch = min((N + KC - 1) / KC, NCH);
     for (int t = threadIdx.x; t < H * nblk * 16; t += 256) {
         const int h = t / (nblk * 16), i = t - h * (nblk * 16);
         float c = INFINITY;
@@ -469,31 +473,33 @@ int d3tom::importance_run(const void* q, const void* k, int dt,
         // small decider sets: the first sweep keeps its logits and the scores come from them (K fetched once)
         const bool keep = max_D <= IMP_KEEP_MAXD;
         float* logits = (float*)(wsb + w.logit_off);
+#define D3TOM_IMP_STATS(DHV, KEEPV, SUBV)                                                                     \
+    D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<DHV, KEEPV, SUBV><<<g1, 256, 0, st>>>(                           \
+        qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)))
+        const bool big = w.KC == IMP_KC_STATS;
+        if (dh == 128) {
+            if (keep) { if (big) D3TOM_IMP_STATS(128, true, 8); else D3TOM_IMP_STATS(128, true, 4); }
+            else      { if (big) D3TOM_IMP_STATS(128, false, 8); else D3TOM_IMP_STATS(128, false, 4); }
+        } else {
+            if (keep) { if (big) D3TOM_IMP_STATS(64, true, 8); else D3TOM_IMP_STATS(64, true, 4); }
+            else      { if (big) D3TOM_IMP_STATS(64, false, 8); else D3TOM_IMP_STATS(64, false, 4); }
+        }
+#undef D3TOM_IMP_STATS
         if (keep) {
-            if (dh == 128)
-                D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<128, true><<<g1, 256, 0, st>>>(
-                    qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
-            else
-                D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<64, true><<<g1, 256, 0, st>>>(
-                    qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
             const dim3 g2k(ceil_div(max_N, 16), B);
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_from_logits<<<g2k, 256, (size_t)H * w.DPAD * sizeof(float), st>>>(
-                H, seq_off, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD, w.NCH, w.NKB, part, logits, scores));
+                H, seq_off, dec_off, vis_start, vis_count, score_off, max_D, max_V, w.DPAD, w.NCH, w.KC, w.NKB, part, logits,
+                scores));
             return D3TOM_OK;
         }
-        if (dh == 128) {
-            D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<128, false><<<g1, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
+        if (dh == 128)
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<128><<<g2, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.VPAD,
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.KC, w.VPAD,
                 part, sp));
-        } else {
-            D3TOM_LAUNCH(IMP_STATS, st, (imp_stats_bf16<64, false><<<g1, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, max_D, w.DPAD, w.NCH, part, w.NKB, logits)));
+        else
             D3TOM_LAUNCH(IMP_SCORES, st, imp_scores_bf16<64><<<g2, 256, 0, st>>>(
-                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.VPAD,
+                qq, kk, H, scale2, seq_off, dec_idx, dec_off, vis_start, vis_count, max_D, max_V, w.DPAD, w.NCH, w.KC, w.VPAD,
                 part, sp));
-        }
         D3TOM_LAUNCH(IMP_FINISH, st, imp_finish_kernel<<<g3, 256, 0, st>>>(
             sp, H, w.VPAD, seq_off, vis_start, vis_count, score_off, max_V, scores));
         return D3TOM_OK;

@@ -507,14 +507,16 @@ def test_stack_full_size_two_blocks_against_oracle(B):
 
 
 def test_stack_trajectory_with_decider_updates(B):
-    """Three denoising steps of a small stack the way the benchmark drives the full one: decider set from two
-    successive token-id states on the device, embedding of the current response tokens, one stack step.
-    Step 0 has no deciders and runs unmerged (Algorithm 1); later steps merge."""
-    L, d, H, F, Pn, V, O, keep_k = 2, 256, 4, 512, 6, 80, 10, 20
+    """A whole denoising trajectory (T = 9 steps) of a small stack the way the benchmark drives the full one:
+    decider set from two successive token-id states on the device, embedding of the current response tokens, one
+    stack step.  Step 0 has no deciders and runs unmerged (Algorithm 1); every later step merges, with a decider
+    set that changes from step to step (one to several newly revealed positions)."""
+    L, d, H, F, Pn, V, O, keep_k = 2, 256, 4, 512, 6, 80, 18, 20
+    T = 9
     case = W.stack_case(91, L=L, d=d, H=H, F=F, P=Pn, V=V, O=O, D=0, std=1.0 / 16, gain_jitter=0.1)
     N = case["N"]
     mask_id = 126336
-    states = W.mask_trajectory(5, Pn + V, O, 3, mask_id)
+    states = W.mask_trajectory(5, Pn + V, O, T, mask_id)
     rng = np.random.default_rng(17)
     table = W.round_to(rng.standard_normal((64, d)).astype(np.float32), "bf16")
     mask_vec = W.round_to(rng.standard_normal(d).astype(np.float32), "bf16")
@@ -526,7 +528,8 @@ def test_stack_trajectory_with_decider_updates(B):
     dec_off = torch.zeros(2, dtype=torch.int32, device="cuda")
     dec_count = torch.zeros(1, dtype=torch.int32, device="cuda")
     merged_steps = 0
-    for s in range(3):
+    sizes = set()
+    for s in range(T):
         x = case["x"].copy()
         ids = states[s][Pn + V:]
         x[Pn + V:] = np.where((ids == mask_id)[:, None], mask_vec[None, :], table[ids % 64])
@@ -538,6 +541,7 @@ def test_stack_trajectory_with_decider_updates(B):
             D = int(dec_count.item())
             dec_ref = oracle.deciders(states[s - 1], states[s], mask_id)
             np.testing.assert_array_equal(dec_idx[:D].cpu().numpy(), dec_ref)
+            sizes.add(D)
         y = torch.zeros(N, d, dtype=torch.bfloat16, device="cuda")
         kept = torch.zeros(keep_k, dtype=torch.int32, device="cuda")
         asg = torch.zeros(V, dtype=torch.int32, device="cuda")
@@ -551,7 +555,8 @@ def test_stack_trajectory_with_decider_updates(B):
         got = _host(y[:n_out])
         rel = np.sqrt(np.mean((got - ref["y"]) ** 2)) / np.sqrt(np.mean(ref["y"] ** 2))
         assert rel < 2e-2, (s, rel)          # 3x the rounding floor measured for two to four blocks
-    assert merged_steps == 2
+        assert (np.abs(got - ref["y"]) - _whole_step_elementwise_bound(ref["y"], L)).max() <= 0
+    assert merged_steps == T - 1 and len(sizes) > 1
 
 
 def test_stack_workspace_contents_do_not_matter(B):
