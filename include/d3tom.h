@@ -405,6 +405,32 @@ int d3tom_stack_step(const void* x, int N, int d, int H, int F, int L, const d3t
                      int32_t* assign_out, int* n_out /* host */, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
+ * d3tom_stack_step_batch — d3tom_stack_step for B samples concatenated along the token axis (Algorithm 1 is
+ * stated per sample; samples only meet in the launches: projections and normalisations run over all rows,
+ * attention and the merge layer per sample).  Per-sample sizes are HOST arrays of B entries (they size the
+ * launches); everything else is as in d3tom_stack_step, with outputs concatenated in sample order.
+ *
+ *   x          [sum N_b, d] bf16
+ *   N, D, vis_start, V, keep_k   host int32[B]; vis_start / V / keep_k may be NULL when no sample has deciders
+ *   dec_idx    device int32[sum D_b], the samples' decider positions (within the sample) back to back
+ *   y          [sum n_out_b, d] out, n_out_b = N_b - (V_b - keep_k[b]) when merging, else N_b
+ *   src_pos    int32[sum n_out_b] out or NULL (positions within the sample)
+ *   scores_out float[sum V_b], kept_idx_out int32[sum keep_k], assign_out int32[sum V_b]: out or NULL
+ *   n_out      HOST int[B] out or NULL
+ * B above D3TOM_STACK_MAX_BATCH returns D3TOM_ERR_UNSUPPORTED.  Inside one batch all samples take the same path:
+ * if some samples have deciders and others none, the call returns D3TOM_ERR_NO_DECIDERS before anything is
+ * enqueued (the caller splits the batch).  Workspace: d3tom_stack_batch_workspace_bytes.
+ * ---------------------------------------------------------------------------------------- */
+#define D3TOM_STACK_MAX_BATCH 64
+size_t d3tom_stack_batch_workspace_bytes(int B, int sum_N, int max_N, int d, int H, int F, int sum_V, int max_V, int max_D);
+int d3tom_stack_step_batch(const void* x, int B, const int32_t* N /* host */, int d, int H, int F, int L,
+                           const d3tom_block_weights* blocks /* host */, int merge_layer, const int32_t* dec_idx,
+                           const int32_t* D /* host */, const int32_t* vis_start /* host */, const int32_t* V /* host */,
+                           const int32_t* keep_k /* host */, int mode, float eps, float theta, void* y, int32_t* src_pos,
+                           float* scores_out, int32_t* kept_idx_out, int32_t* assign_out, int* n_out /* host */,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------------------------
  * Per-kernel timing (diagnostics; used by the benchmark for its roofline figures).  While enabled,
  * every kernel launch of the four entry points is bracketed by HIP events on the caller's stream.
  * d3tom_profile_collect waits for the recorded events, adds up milliseconds and launch counts per

@@ -33,7 +33,7 @@ D3TOM_LINEAR_PLAIN, D3TOM_LINEAR_RESIDUAL, D3TOM_LINEAR_SWIGLU = range(3)
 
 EXPORTS = ["d3tom_keep_count", "d3tom_schedule", "d3tom_model_flops", "d3tom_workspace_bytes",
            "d3tom_status_string", "d3tom_importance", "d3tom_importance_static", "d3tom_select_topk", "d3tom_merge", "d3tom_merge_kv", "d3tom_merge_layer_workspace_bytes", "d3tom_merge_layer", "d3tom_attend", "d3tom_attend_weighted", "d3tom_update_deciders",
-           "d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_linear_tile", "d3tom_stack_workspace_bytes", "d3tom_stack_step",
+           "d3tom_rmsnorm", "d3tom_rope", "d3tom_linear", "d3tom_linear_tile", "d3tom_stack_workspace_bytes", "d3tom_stack_step", "d3tom_stack_batch_workspace_bytes", "d3tom_stack_step_batch",
            "d3tom_profile_enable", "d3tom_profile_kernel_count", "d3tom_profile_kernel_name", "d3tom_profile_collect"]
 
 _vp, _i, _f, _d, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_double, ctypes.c_size_t
@@ -91,6 +91,13 @@ _lib.d3tom_stack_workspace_bytes.argtypes = [_i] * 6
 _lib.d3tom_stack_step.restype = _i
 _lib.d3tom_stack_step.argtypes = [_vp, _i, _i, _i, _i, _i, ctypes.POINTER(BlockWeights), _i, _vp, _i, _i, _i, _i, _i,
                                   _f, _f, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i), _vp, _sz, _vp]
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_lib.d3tom_stack_batch_workspace_bytes.restype = _sz
+_lib.d3tom_stack_batch_workspace_bytes.argtypes = [_i] * 9
+_lib.d3tom_stack_step_batch.restype = _i
+_lib.d3tom_stack_step_batch.argtypes = [_vp, _i, _i32p, _i, _i, _i, _i, ctypes.POINTER(BlockWeights), _i, _vp, _i32p, _i32p, _i32p,
+                                        _i32p, _i, _f, _f, _vp, _vp, _vp, _vp, _vp, ctypes.POINTER(_i), _vp, _sz, _vp]
 
 _lib.d3tom_profile_enable.restype = _i
 _lib.d3tom_profile_enable.argtypes = [_i]
@@ -406,6 +413,29 @@ def d3tom_stack_step(x: torch.Tensor, H: int, F: int, blocks, L: int, merge_laye
                                  ctypes.byref(n_out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
            "d3tom_stack_step")
     return n_out.value
+
+
+def d3tom_stack_batch_workspace_bytes(B: int, sum_N: int, max_N: int, d: int, H: int, F: int, sum_V: int, max_V: int,
+                                      max_D: int) -> int:
+    return int(_lib.d3tom_stack_batch_workspace_bytes(B, sum_N, max_N, d, H, F, sum_V, max_V, max_D))
+
+
+def d3tom_stack_step_batch(x: torch.Tensor, N: Sequence[int], H: int, F: int, blocks, L: int, merge_layer: int,
+                           dec_idx: Optional[torch.Tensor], D: Sequence[int], vis_start: Sequence[int], V: Sequence[int],
+                           keep_k: Sequence[int], mode: int, eps: float, theta: float, y: torch.Tensor, ws: torch.Tensor,
+                           src_pos: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                           kept_idx: Optional[torch.Tensor] = None, assign: Optional[torch.Tensor] = None, stream=None) -> List[int]:
+    """Returns the number of output rows of every sample.  Per-sample sizes are host lists."""
+    Bn = len(N)
+    assert x.shape[0] == sum(N) and len(D) == Bn and len(vis_start) == Bn and len(V) == Bn and len(keep_k) == Bn
+    d = x.shape[1]
+    arr = lambda a: (ctypes.c_int32 * Bn)(*[int(v) for v in a])
+    n_out = (ctypes.c_int * Bn)()
+    _check(_lib.d3tom_stack_step_batch(_ptr(x), Bn, arr(N), d, H, F, L, blocks, merge_layer, _ptr(dec_idx), arr(D), arr(vis_start),
+                                       arr(V), arr(keep_k), mode, eps, theta, _ptr(y), _ptr(src_pos), _ptr(scores), _ptr(kept_idx),
+                                       _ptr(assign), n_out, _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)),
+           "d3tom_stack_step_batch")
+    return [int(v) for v in n_out]
 
 
 def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:

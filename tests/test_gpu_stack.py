@@ -559,6 +559,62 @@ def test_stack_trajectory_with_decider_updates(B):
     assert merged_steps == T - 1 and len(sizes) > 1
 
 
+def test_stack_step_batch_of_ragged_samples(B):
+    """Three samples of different lengths, visual blocks, decider counts and keep counts through one call: every
+    sample's output against the oracle's step of that sample alone (on the kept set and assignment the GPU chose,
+    which must agree with a single-sample GPU run up to near-threshold swaps); a batch that mixes samples with and
+    without deciders is refused; a batch without any deciders runs unmerged."""
+    L, d, H, F = 2, 256, 4, 512
+    specs = [(8, 200, 12, 5, 50), (0, 96, 30, 9, 24), (20, 333, 7, 2, 111)]        # P, V, O, D, keep
+    base = W.stack_case(95, L=L, d=d, H=H, F=F, P=1, V=8, O=1, D=1, std=1.0 / 16, gain_jitter=0.1)   # the shared weights
+    cases = []
+    for i, (Pn, V, O, D, k) in enumerate(specs):
+        c = W.stack_case(96 + i, L=L, d=d, H=H, F=F, P=Pn, V=V, O=O, D=D, std=1.0 / 16, gain_jitter=0.1)
+        cases.append(dict(c, blocks=base["blocks"]))
+    gb = _gpu_blocks(base)
+    arr = B.block_weights(gb)
+    Ns = [c["N"] for c in cases]; Vs = [c["V"] for c in cases]; Ds = [c["D"] for c in cases]
+    vss = [c["vis_start"] for c in cases]; ks = [sp[4] for sp in specs]
+    x = _dev(np.concatenate([c["x"] for c in cases]))
+    dec = torch.from_numpy(np.concatenate([c["dec_idx"] for c in cases])).cuda()
+    ws = B.workspace(B.d3tom_stack_batch_workspace_bytes(3, sum(Ns), max(Ns), d, H, F, sum(Vs), max(Vs), max(Ds)))
+    ws.fill_(255)
+    y = torch.zeros(sum(Ns), d, dtype=torch.bfloat16, device="cuda")
+    src = torch.full((sum(Ns),), -1, dtype=torch.int32, device="cuda")
+    kept = torch.zeros(sum(ks), dtype=torch.int32, device="cuda")
+    asg = torch.zeros(sum(Vs), dtype=torch.int32, device="cuda")
+    n_out = B.d3tom_stack_step_batch(x, Ns, H, F, arr, L, 1, dec, Ds, vss, Vs, ks, 0, 1e-5, 10000.0, y, ws, src_pos=src,
+                                     kept_idx=kept, assign=asg)
+    torch.cuda.synchronize()
+    assert n_out == [n - (v - k) for n, v, k in zip(Ns, Vs, ks)]
+    yo = np.split(_host(y[:sum(n_out)]), np.cumsum(n_out)[:-1])
+    so = np.split(src[:sum(n_out)].cpu().numpy(), np.cumsum(n_out)[:-1])
+    ko = np.split(kept.cpu().numpy(), np.cumsum(ks)[:-1])
+    ao = np.split(asg.cpu().numpy(), np.cumsum(Vs)[:-1])
+    rms = lambda a_, b_: np.sqrt(np.mean((a_ - b_) ** 2)) / np.sqrt(np.mean(b_ ** 2))
+    for b, c in enumerate(cases):
+        ref = stack_step_given(c["x"], _oracle_blocks(c), H, c["dec_idx"], c["vis_start"], c["V"], ks[b], 1, kept=ko[b], assign=ao[b])
+        alt = stack_step_given(c["x"], _oracle_blocks(c), H, c["dec_idx"], c["vis_start"], c["V"], ks[b], 1, kept=ko[b], assign=ao[b],
+                               store=jittered_bf16(3e-7, 1))
+        np.testing.assert_array_equal(so[b], ref["src_pos"])
+        assert rms(yo[b], ref["y"]) <= 3.0 * rms(alt["y"], ref["y"]) + 1e-4
+        assert (np.abs(yo[b] - ref["y"]) - _whole_step_elementwise_bound(ref["y"], L)).max() <= 0
+        one = _run_stack(B, c, ks[b], 1)                       # the same sample alone through d3tom_stack_step
+        assert len(np.setxor1d(one["kept"], ko[b])) <= 2
+    # mixed batch: refused before anything runs; no deciders at all: every sample at full length
+    with pytest.raises(B.D3tomError) as e:
+        B.d3tom_stack_step_batch(x, Ns, H, F, arr, L, 1, dec, [Ds[0], 0, Ds[2]], vss, Vs, ks, 0, 1e-5, 10000.0, y, ws)
+    assert e.value.status == B.D3TOM_ERR_NO_DECIDERS
+    n_out = B.d3tom_stack_step_batch(x, Ns, H, F, arr, L, 1, None, [0, 0, 0], vss, Vs, ks, 0, 1e-5, 10000.0, y, ws)
+    torch.cuda.synchronize()
+    assert n_out == Ns
+    full = np.split(_host(y), np.cumsum(Ns)[:-1])
+    for b, c in enumerate(cases):
+        ref = OS.stack_step(c["x"], _oracle_blocks(c), H, None, c["vis_start"], c["V"], ks[b], 1)
+        alt = OS.stack_step(c["x"], _oracle_blocks(c), H, None, c["vis_start"], c["V"], ks[b], 1, store=jittered_bf16(3e-7))
+        assert rms(full[b], ref["y"]) <= 3.0 * rms(alt["y"], ref["y"]) + 1e-4
+
+
 def test_stack_workspace_contents_do_not_matter(B):
     case = W.stack_case(93, L=2, d=2048, H=16, F=2048, P=6, V=90, O=8, D=4, std=1.0 / 45, gain_jitter=0.1)
     N, d, H, F, V = case["N"], 2048, 16, 2048, 90
