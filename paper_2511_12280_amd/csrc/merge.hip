@@ -148,7 +148,8 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
 // run covers a compact block of about RB x (run / RB) tiles, so its private L2 sees few operand rows.
 // The loads are buffer loads: each lane's byte offset (row and swizzled chunk) is fixed for the whole
 // sweep and the k-slice moves through the scalar offset, so a stage costs no address arithmetic.
-constexpr int COS_NS = 4;
+constexpr int cos_ring_stages(int TM) { return TM >= 4 ? 3 : 4; }     // 256-row tiles: 3 stages of 48 KB fit the 160 KB of LDS
+constexpr int COS_NS_MIN = 3;
 
 template <int TM>
 __global__ __launch_bounds__(512) void cos_argmax_bf16(
@@ -158,6 +159,7 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     table_t* __restrict__ table, int VP, int per, int RB, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BM = TM * 64;
+    constexpr int COS_NS = cos_ring_stages(TM);
     constexpr int STAGE = (BM + COS_BN) * 128;          // bytes per ring stage (64 bf16 = 128 B per row)
     constexpr int A_LD = BM / 32;                       // direct loads per wave and stage, A tile (8 rows each)
     constexpr int B_LD = COS_BN / 32;
@@ -316,26 +318,11 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     }
     // epilogue: dot * rn_col (the cosine up to the row's own positive norm, which is the same for all of
     // its candidates); per row, best (value, slot) over this tile's columns.
-    // Branch-free selects, and all rows advance through each exchange step together, so the 32
-    // independent cross-lane exchanges of a step are in flight at once.
-    float bv[TM][16];
-    int bi[TM][16];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-            const int col0 = wn * 64 + c, col1 = col0 + 32;
-            const int s0 = ct * COS_BN + col0, s1 = s0 + 32;
-            const float v0 = (s0 < s.k) ? acc[i][0][e] * rnB[col0] : -INFINITY;
-            const float v1 = (s1 < s.k) ? acc[i][1][e] * rnB[col1] : -INFINITY;
-            const bool t1 = v1 > v0;                       // equal values: the lower slot stays
-            bv[i][e] = t1 ? v1 : v0;
-            bi[i][e] = t1 ? s1 : s0;
-        }
-    // The 64 candidates of a row (32 lanes x 2 wave columns) meet in LDS (the ring is free now): every
-    // lane stores its 16*TM candidates, then two threads per row scan 32 candidates each in ascending slot
-    // order.  Rows are padded to 33 entries so that the scan of 32 different rows hits 32 different banks.
+    // The 64 candidates of a row (32 lanes x 2 wave columns) meet in LDS (the ring is free once all waves
+    // are past the loop): every lane folds its two columns of a row into one candidate (branch-free; equal
+    // values keep the lower slot) and stores it, then two threads per row scan 32 candidates each in
+    // ascending slot order.  Rows are padded to 33 entries so that the scan of 32 different rows hits 32
+    // different banks.
     __syncthreads();                                           // all waves are done with the ring
     float2* cand = reinterpret_cast<float2*>(ring);            // [BM][2][33]
     if (!loader) {
@@ -344,7 +331,12 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int row = wm * (TM * 32) + i * 32 + (e >> 2) * 8 + g * 4 + (e & 3);
-                cand[(row * 2 + wn) * 33 + c] = make_float2(bv[i][e], __int_as_float(bi[i][e]));
+                const int col0 = wn * 64 + c, col1 = col0 + 32;
+                const int s0 = ct * COS_BN + col0, s1 = s0 + 32;
+                const float v0 = (s0 < s.k) ? acc[i][0][e] * rnB[col0] : -INFINITY;
+                const float v1 = (s1 < s.k) ? acc[i][1][e] * rnB[col1] : -INFINITY;
+                const bool t1 = v1 > v0;                       // equal values: the lower slot stays
+                cand[(row * 2 + wn) * 33 + c] = make_float2(t1 ? v1 : v0, __int_as_float(t1 ? s1 : s0));
             }
     }
     __syncthreads();
@@ -697,8 +689,9 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
 
     static PerDeviceOnce lds_setup;
     if (!lds_setup.run([] {
-            return raise_dynamic_lds(cos_argmax_bf16<1>, COS_NS * (64 + COS_BN) * 128) &&
-                   raise_dynamic_lds(cos_argmax_bf16<2>, COS_NS * (128 + COS_BN) * 128);
+            return raise_dynamic_lds(cos_argmax_bf16<1>, cos_ring_stages(1) * (64 + COS_BN) * 128) &&
+                   raise_dynamic_lds(cos_argmax_bf16<2>, cos_ring_stages(2) * (128 + COS_BN) * 128) &&
+                   raise_dynamic_lds(cos_argmax_bf16<4>, cos_ring_stages(4) * (256 + COS_BN) * 128);
         }))
         return D3TOM_ERR_DEVICE;
 
@@ -717,7 +710,8 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         const int nct = ceil_div(max_keep, COS_BN);
         // as long as the 64-row tiles still fit one round of the 256 CUs they finish sooner than half as many
         // 128-row tiles (a 64-row tile's k-loop is ~0.7 of a 128-row tile's)
-        const int TM = ((long)nct * ceil_div(max_pruned, 64) * B > 256) ? 2 : 1;
+        // with several rounds of 128-row tiles (large batches) 256-row tiles move a third less operand data per flop
+        const int TM = ((long)nct * ceil_div(max_pruned, 128) * B > 768) ? 4 : ((long)nct * ceil_div(max_pruned, 64) * B > 256) ? 2 : 1;
         // too few 64 x 128 tiles for 256 CUs (short sequences): cut the contraction into k-slices as well
         int ksplit = 1;
         if (TM == 1) {
@@ -725,7 +719,7 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
             const int stages = d_sim / COS_BK;
             if (tiles <= COS_SPLIT_BLOCKS / 2) {
                 ksplit = 16;
-                while (ksplit > 1 && (tiles * ksplit > COS_SPLIT_BLOCKS || stages % ksplit || stages / ksplit < COS_NS)) ksplit >>= 1;
+                while (ksplit > 1 && (tiles * ksplit > COS_SPLIT_BLOCKS || stages % ksplit || stages / ksplit < cos_ring_stages(1))) ksplit >>= 1;
             }
         }
         const int BM = TM * 64;
@@ -737,8 +731,12 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         if (RB > nrt) RB = nrt;
         const dim3 g((unsigned)(8 * per * B), (unsigned)ksplit);
         float* dots = (float*)(wsb + w.dots_off);
-        const size_t lds = (size_t)COS_NS * (BM + COS_BN) * 128;
-        if (TM == 1)
+        const size_t lds = (size_t)cos_ring_stages(TM) * (BM + COS_BN) * 128;
+        if (TM == 4)
+            D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<4><<<g, 512, lds, st>>>(
+                (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
+                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct));
+        else if (TM == 1)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
                 rnorm, table, w.VP, per, RB, ksplit, dots, nrt, nct));
