@@ -87,6 +87,15 @@ __device__ __forceinline__ void lse2_combine(float& m, float& z, float m2, float
     m = mn; z = a + b;
 }
 
+// The same with the hardware exponential (one instruction, about 1 ulp, results below the normal range flush to
+// zero): for the MFMA kernels, whose workgroups combine hundreds of pairs each.
+__device__ __forceinline__ void lse2_combine_fast(float& m, float& z, float m2, float z2) {
+    float mn = fmaxf(m, m2);
+    float a = (m == -INFINITY) ? 0.f : z * __builtin_amdgcn_exp2f(m - mn);
+    float b = (m2 == -INFINITY) ? 0.f : z2 * __builtin_amdgcn_exp2f(m2 - mn);
+    m = mn; z = a + b;
+}
+
 __host__ __device__ __forceinline__ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 __host__ __device__ __forceinline__ size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 

@@ -164,7 +164,7 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
     for (int t = threadIdx.x; t < nblk * 16; t += 256) {
         float2 a = wstat[0][t];
 #pragma unroll
-        for (int w = 1; w < 4; ++w) lse2_combine(a.x, a.y, wstat[w][t].x, wstat[w][t].y);
+        for (int w = 1; w < 4; ++w) lse2_combine_fast(a.x, a.y, wstat[w][t].x, wstat[w][t].y);
         part[((size_t)(b * H + h) * NCH + chunk) * DPAD + t] = a;
     }
 }
@@ -203,9 +203,9 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
 #pragma unroll
             for (int u = 0; u < 16; ++u) a[u] = (c0 + u < nch) ? p[(size_t)(c0 + u) * DPAD] : make_float2(-INFINITY, 0.f);
 #pragma unroll
-            for (int u = 0; u < 16; ++u) lse2_combine(m, z, a[u].x, a[u].y);
+            for (int u = 0; u < 16; ++u) lse2_combine_fast(m, z, a[u].x, a[u].y);
         }
-        c_lds[t] = m + log2f(z);
+        c_lds[t] = m + __builtin_amdgcn_logf(z);
     }
     bf16x8 kf[IMP_SUB_SCORES][KS];
     float acc_s[IMP_SUB_SCORES];
@@ -305,9 +305,10 @@ __global__ __launch_bounds__(256) void imp_scores_from_logits(
 #pragma unroll
                 for (int u = 0; u < 8; ++u) a[u] = (c0 + u < nch) ? p[(size_t)(c0 + u) * DPAD] : make_float2(-INFINITY, 0.f);
 #pragma unroll
-                for (int u = 0; u < 8; ++u) lse2_combine(m, z, a[u].x, a[u].y);
+                for (int u = 0; u < 8; ++u)
+                    if (c0 + u < nch) lse2_combine_fast(m, z, a[u].x, a[u].y);
             }
-            c = m + log2f(z);
+            c = m + __builtin_amdgcn_logf(z);
         }
         c_lds[h * DPAD + i] = c;
     }
