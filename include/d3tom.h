@@ -295,7 +295,7 @@ int d3tom_attend_weighted(const void* q, const void* k, const void* v, int dt,
                           void* o, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------------------------
- * d3tom_update_deciders — the decider set for the next merge (Section 3.1, "The Decider-Guided
+ * d3tom_update_deciders — the decider set for the next merge (Section 3.2, "The Decider-Guided
  * Mechanism": D = { positions that hold a token now and held [MASK] in the preceding iteration };
  * Algorithm 1, the last line of the denoising loop; an empty set means "run this step unmerged").
  *

@@ -45,7 +45,7 @@ int oracle_keep_count(int V, double keep_ratio) {
     return (int)c;
 }
 
-/* Decider set (Section 3.1, "The Decider-Guided Mechanism"): the positions that
+/* Decider set (Section 3.2, "The Decider-Guided Mechanism"): the positions that
  * hold a token in the current iterate and held [MASK] in the preceding one,
  * listed in ascending position.  Returns their number; at most `cap` are
  * written to out. */

@@ -1,4 +1,4 @@
-// d3tom_update_deciders: the decider set of the next step (Section 3.1, "The Decider-Guided Mechanism":
+// d3tom_update_deciders: the decider set of the next step (Section 3.2, "The Decider-Guided Mechanism":
 // the tokens revealed in the preceding iteration, i.e. positions that hold a token now and held [MASK]
 // one iteration earlier; Algorithm 1, the last line of the denoising loop).
 //

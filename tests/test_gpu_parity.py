@@ -479,7 +479,7 @@ def test_merge_kv_ragged_batch(mode):
         np.testing.assert_array_equal(ref["assign"][b], out["assign"][b])
 
 
-# ---- decider bookkeeping on the device (Section 3.1) ----------------------------------------------------
+# ---- decider bookkeeping on the device (Section 3.2) ----------------------------------------------------
 def test_update_deciders_batch_and_chain_into_importance():
     M = 126336
     specs = [(300, 64, 9), (1152 - 64, 64, 5), (0, 1500, 4), (2688 - 256, 256, 2), (10, 1, 1)]     # (prefix, response, steps)

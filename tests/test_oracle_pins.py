@@ -502,7 +502,7 @@ def test_cost_model_merge_overhead_term():
 
 
 # --------------------------------------------------------------------------------------
-# decider bookkeeping (Section 3.1; Algorithm 1, the update after every step)
+# decider bookkeeping (Section 3.2; Algorithm 1, the update after every step)
 # --------------------------------------------------------------------------------------
 def test_deciders_definition_on_a_written_out_example():
     M = 9
