@@ -137,12 +137,36 @@ __global__ __launch_bounds__(256) void rope_bf16_kernel(uint16_t* __restrict__ q
         for (int e = 0; e < 4; ++e) {
             const int c0 = cc * 8 + 2 * e;
             const float a0 = bf16_lo(aw[e]), a1 = bf16_hi(aw[e]), b0 = bf16_lo(bw[e]), b1 = bf16_hi(bw[e]);
-            ao[e] = pack_bf16x2(a0 * cs[c0] - b0 * sn[c0], a1 * cs[c0 + 1] - b1 * sn[c0 + 1]);
-            bo[e] = pack_bf16x2(b0 * cs[c0] + a0 * sn[c0], b1 * cs[c0 + 1] + a1 * sn[c0 + 1]);
+            float ra0, rb0, ra1, rb1;
+            rope_rotate(a0, b0, cs[c0], sn[c0], ra0, rb0);
+            rope_rotate(a1, b1, cs[c0 + 1], sn[c0 + 1], ra1, rb1);
+            ao[e] = pack_bf16x2(ra0, ra1);
+            bo[e] = pack_bf16x2(rb0, rb1);
         }
         *reinterpret_cast<uint4*>(pa) = make_uint4(ao[0], ao[1], ao[2], ao[3]);
         *reinterpret_cast<uint4*>(pa + half) = make_uint4(bo[0], bo[1], bo[2], bo[3]);
     }
+}
+
+// (cos, sin) of every token's dh/2 rotary angles, the float32 values the kernel above uses: for the projection
+// epilogue that applies the rotation itself (one table per step instead of one rotary launch per block)
+__global__ __launch_bounds__(256) void rope_table_kernel(const int32_t* __restrict__ pos, int rows, int dh, double log2_theta,
+                                                         float2* __restrict__ table) {
+    const int half = dh >> 1;
+    const int t = blockIdx.x * 256 + threadIdx.x;
+    if (t >= rows * half) return;
+    const int r = t / half, c = t - r * half;
+    const double inv_freq = exp2(-2.0 * (double)c / (double)dh * log2_theta);
+    double s, co;
+    sincos((double)pos[r] * inv_freq, &s, &co);
+    table[t] = make_float2((float)co, (float)s);
+}
+
+int rope_table_run(const int32_t* pos, int rows, int dh, float theta, float2* table, hipStream_t st) {
+    if (!pos || !table || rows < 1 || dh < 2) return D3TOM_ERR_INVALID_ARG;
+    if (!(theta > 1.f) || !(theta < 3.0e38f)) return D3TOM_ERR_INVALID_ARG;
+    D3TOM_LAUNCH(ROPE, st, (rope_table_kernel<<<ceil_div(rows * (dh >> 1), 256), 256, 0, st>>>(pos, rows, dh, log2((double)theta), table)));
+    return D3TOM_OK;
 }
 
 int rmsnorm_run(const void* x, const void* gain, int rows, int d, float eps, void* y, hipStream_t st) {

@@ -87,6 +87,13 @@ __device__ __forceinline__ void lse2_combine(float& m, float& z, float m2, float
     m = mn; z = a + b;
 }
 
+// One rotary pair (a, b) turned by the angle with cosine c and sine s.  The fused multiply-adds are spelled out so
+// that every kernel that rotates (the rotary kernel, the q | k | v projection's epilogue) rounds the same way.
+__device__ __forceinline__ void rope_rotate(float a, float b, float c, float s, float& ra, float& rb) {
+    ra = __builtin_fmaf(a, c, -(b * s));
+    rb = __builtin_fmaf(b, c, a * s);
+}
+
 // The same with the hardware exponential (one instruction, about 1 ulp, results below the normal range flush to
 // zero): for the MFMA kernels, whose workgroups combine hundreds of pairs each.
 __device__ __forceinline__ void lse2_combine_fast(float& m, float& z, float m2, float z2) {

@@ -4,11 +4,15 @@
 //   PLAIN     out = a w^T, optionally written as several [rows, out_chunk] matrices (q | k | v)
 //   RESIDUAL  out = residual + a w^T                      (the block's two skip connections)
 //   SWIGLU    out = silu(a w_gate^T) * (a w_up^T)         (w holds the F gate rows, then the F up rows)
-// One rounding to bf16, at the store.
+//   ROPE      (inside the stack only) PLAIN for the stacked q | k | v weight with the rotary embedding of the q and k
+//             sections folded in: a 128-column tile holds whole heads, so both channels of a rotation pair are in
+//             the tile; the projection is rounded to bf16 first (the value the separate rotary kernel would have
+//             read), turned by the token's angle from a per-step table, and rounded again
 //   PARTIAL   (inside the stack only) the contraction is cut into gridDim.y slices and every slice writes
 //             its float32 products to its own [rows, n] matrix; the row-wise kernel that follows adds the
 //             slices, the residual, rounds once and normalises.  Used where a short sequence leaves the
 //             output and down projections with too few tall tiles to fill the chip.
+// One rounding to bf16, at the store (ROPE: one for the projection, one for the rotated value).
 //
 // Workgroup tile: (TM*64) rows x 128 columns of a w^T.  Eight waves with two jobs: waves 0..3 (2 x 2, wave
 // tile (TM*32) x 64) only feed the matrix cores, waves 4..7 only move data.  Both operands are
@@ -29,7 +33,7 @@
 
 namespace d3tom {
 
-enum { LIN_PLAIN = 0, LIN_RESIDUAL = 1, LIN_SWIGLU = 2, LIN_PARTIAL = 3 };
+enum { LIN_PLAIN = 0, LIN_RESIDUAL = 1, LIN_SWIGLU = 2, LIN_PARTIAL = 3, LIN_ROPE = 4 };
 constexpr int LIN_BN = 128;
 constexpr int LIN_BK = 64;
 constexpr int LIN_PAD = 136;      // floats per row of the epilogue staging tile (see the epilogue)
@@ -44,7 +48,8 @@ template <int TM> struct LinCfg {
 template <int TM, int EPI>
 __global__ __launch_bounds__(512) void linear_bf16_kernel(
     const uint16_t* __restrict__ a, const uint16_t* __restrict__ w, int M, int N, int K,
-    const uint16_t* residual, uint16_t* out, int out_chunk, int NRT, int NCT, int cpx, int PC, int col0, int col_end) {
+    const uint16_t* residual, uint16_t* out, int out_chunk, int NRT, int NCT, int cpx, int PC, int col0, int col_end,
+    const float2* __restrict__ rope_cs, int rope_dh) {
 #if defined(__HIP_DEVICE_COMPILE__)
     using C = LinCfg<TM>;
     constexpr int BM = C::BM, NS = C::NS, STAGE = C::STAGE;
@@ -188,6 +193,49 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
                 }
     }
     __syncthreads();
+    if constexpr (EPI == LIN_ROPE) {
+        // A unit is an 8-column group of the first half of a head together with its partner group half a head
+        // further: the two share their angles, so one thread rotates both (one table read for 16 outputs).  Heads
+        // start at multiples of their size, so a 128-column tile holds whole heads.
+        const int half = rope_dh >> 1, gph = half >> 3;                // 8-column groups in half a head: 8 or 4
+        constexpr int UPR = OUT_BN / 16;                               // units per tile row
+        for (int u = tid; u < BM * UPR; u += NT) {
+            const int row = u / UPR, un = u % UPR;
+            const int hd = un / gph, gi = un - hd * gph;
+            const int tc = hd * rope_dh + gi * 8;                      // tile column of the first-half group
+            const int m = rt * BM + row, col = col0 + ct * OUT_BN + tc;
+            if (m >= M || col >= col_end) continue;
+            const float* pa = tile + row * LIN_PAD + tc;
+            const float4 a0 = *reinterpret_cast<const float4*>(pa), a1 = *reinterpret_cast<const float4*>(pa + 4);
+            const float4 b0 = *reinterpret_cast<const float4*>(pa + half), b1 = *reinterpret_cast<const float4*>(pa + half + 4);
+            float va[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            float vb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+            if (col < 2 * out_chunk) {                                 // q and k sections; v passes through
+                const float4* cs = reinterpret_cast<const float4*>(rope_cs + (size_t)m * half + gi * 8);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float4 t = cs[e];                            // (cos, sin) of channels 2e and 2e + 1
+                    const float cc[2] = {t.x, t.z}, ss[2] = {t.y, t.w};
+#pragma unroll
+                    for (int f = 0; f < 2; ++f) {
+                        // both channels as the stored bf16 projection, then the rotation in float32
+                        const float x0 = bf16_bits_to_f32(f32_to_bf16_bits(va[2 * e + f]));
+                        const float x1 = bf16_bits_to_f32(f32_to_bf16_bits(vb[2 * e + f]));
+                        rope_rotate(x0, x1, cc[f], ss[f], va[2 * e + f], vb[2 * e + f]);
+                    }
+                }
+            }
+            const size_t o = (size_t)(col / out_chunk) * M * out_chunk + (size_t)m * out_chunk + col % out_chunk;
+            uint4 pk;
+            pk.x = pack_bf16x2(va[0], va[1]); pk.y = pack_bf16x2(va[2], va[3]);
+            pk.z = pack_bf16x2(va[4], va[5]); pk.w = pack_bf16x2(va[6], va[7]);
+            *reinterpret_cast<uint4*>(out + o) = pk;
+            pk.x = pack_bf16x2(vb[0], vb[1]); pk.y = pack_bf16x2(vb[2], vb[3]);
+            pk.z = pack_bf16x2(vb[4], vb[5]); pk.w = pack_bf16x2(vb[6], vb[7]);
+            *reinterpret_cast<uint4*>(out + o + half) = pk;
+        }
+        return;
+    }
     constexpr int CG = OUT_BN / 8;                         // 8-column groups per tile row
     for (int u = tid; u < BM * CG; u += NT) {
         const int row = u / CG, cg = u % CG;
@@ -227,7 +275,7 @@ __global__ __launch_bounds__(512) void linear_bf16_kernel(
 namespace {
 template <int TM, int EPI>
 int launch_linear(const void* a, const void* w, int M, int N, int K, const void* residual, void* out, int out_chunk,
-                  int ksplit, int col0, int col_end, hipStream_t st) {
+                  int ksplit, int col0, int col_end, hipStream_t st, const float2* rope_cs = nullptr, int rope_dh = 0) {
     using C = LinCfg<TM>;
     static PerDeviceOnce lds_setup;      // per instantiation
     if (!lds_setup.run([] { return raise_dynamic_lds(linear_bf16_kernel<TM, EPI>, C::LDS); })) return D3TOM_ERR_DEVICE;
@@ -241,17 +289,17 @@ int launch_linear(const void* a, const void* w, int M, int N, int K, const void*
     const dim3 grid(8u * (unsigned)(panels * PC * NRT), (unsigned)ksplit);
     D3TOM_LAUNCH(LINEAR, st, (linear_bf16_kernel<TM, EPI><<<grid, 512, C::LDS, st>>>(
         (const uint16_t*)a, (const uint16_t*)w, M, N, K, (const uint16_t*)residual, (uint16_t*)out, out_chunk,
-        NRT, NCT, cpx, PC, col0, col_end)));
+        NRT, NCT, cpx, PC, col0, col_end, rope_cs, rope_dh)));
     return D3TOM_OK;
 }
 
 template <int EPI>
 int launch_linear_tm(int tm, const void* a, const void* w, int M, int N, int K, const void* residual, void* out,
-                     int out_chunk, int col0, int col_end, hipStream_t st) {
+                     int out_chunk, int col0, int col_end, hipStream_t st, const float2* rope_cs = nullptr, int rope_dh = 0) {
     switch (tm) {
-        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st);
-        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st);
-        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st);
+        case 1: return launch_linear<1, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st, rope_cs, rope_dh);
+        case 2: return launch_linear<2, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st, rope_cs, rope_dh);
+        default: return launch_linear<4, EPI>(a, w, M, N, K, residual, out, out_chunk, 1, col0, col_end, st, rope_cs, rope_dh);
     }
 }
 }  // namespace
@@ -315,10 +363,15 @@ int linear_partial_run(const void* a, const void* w, int M, int N, int K, int ks
     return launch_linear<4, LIN_PARTIAL>(a, w, M, N, K, nullptr, partial, N, ksplit, 0, N, st);
 }
 
+// rope_cs != nullptr (PLAIN only, stacked q | k | v weight with out_chunk = d, head size rope_dh of 64 or 128): the
+// rotary embedding of the q and k sections is applied in the epilogue; rope_cs[row * rope_dh / 2 + c] = (cos, sin)
 int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, const void* residual, void* out,
-               int out_chunk, int tm_override, hipStream_t st) {
+               int out_chunk, int tm_override, hipStream_t st, const float2* rope_cs, int rope_dh) {
     if (!a || !w || !out || M < 1 || N < 1 || K < 1) return D3TOM_ERR_INVALID_ARG;
     if (epilogue < LIN_PLAIN || epilogue > LIN_SWIGLU) return D3TOM_ERR_INVALID_ARG;
+    if (rope_cs && (epilogue != LIN_PLAIN || (rope_dh != 64 && rope_dh != 128) || out_chunk <= 0 || out_chunk % rope_dh != 0 ||
+                    N != 3 * out_chunk))
+        return D3TOM_ERR_INVALID_ARG;
     if (epilogue == LIN_RESIDUAL && !residual) return D3TOM_ERR_INVALID_ARG;
     if (!aligned16(a) || !aligned16(w) || !aligned16(out) || (residual && !aligned16(residual))) return D3TOM_ERR_INVALID_ARG;
     if (K % LIN_BK != 0) return D3TOM_ERR_UNSUPPORTED;
@@ -333,7 +386,9 @@ int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, 
     const int out_bn = (epilogue == LIN_SWIGLU) ? 64 : 128;
     auto launch = [&](int tm, int col0, int col_end) {
         switch (epilogue) {
-            case LIN_PLAIN: return launch_linear_tm<LIN_PLAIN>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
+            case LIN_PLAIN:
+                if (rope_cs) return launch_linear_tm<LIN_ROPE>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st, rope_cs, rope_dh);
+                return launch_linear_tm<LIN_PLAIN>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
             case LIN_RESIDUAL: return launch_linear_tm<LIN_RESIDUAL>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
             default: return launch_linear_tm<LIN_SWIGLU>(tm, a, w, M, N, K, residual, out, out_chunk, col0, col_end, st);
         }
@@ -350,12 +405,12 @@ int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, 
 
 extern "C" int d3tom_linear(const void* a, const void* w, int rows, int n_w_rows, int K, int epilogue,
                             const void* residual, void* out, int out_chunk, void* stream) {
-    return d3tom::linear_run(a, w, rows, n_w_rows, K, epilogue, residual, out, out_chunk, 0, (hipStream_t)stream);
+    return d3tom::linear_run(a, w, rows, n_w_rows, K, epilogue, residual, out, out_chunk, 0, (hipStream_t)stream, nullptr, 0);
 }
 
 // Same as d3tom_linear with the row-tile height fixed (64, 128 or 256 rows: tile = 1, 2, 4); for tuning.
 extern "C" int d3tom_linear_tile(const void* a, const void* w, int rows, int n_w_rows, int K, int epilogue,
                                  const void* residual, void* out, int out_chunk, int tile, void* stream) {
     if (tile != 1 && tile != 2 && tile != 4) return D3TOM_ERR_INVALID_ARG;
-    return d3tom::linear_run(a, w, rows, n_w_rows, K, epilogue, residual, out, out_chunk, tile, (hipStream_t)stream);
+    return d3tom::linear_run(a, w, rows, n_w_rows, K, epilogue, residual, out, out_chunk, tile, (hipStream_t)stream, nullptr, 0);
 }

@@ -6,7 +6,8 @@
 
 namespace d3tom {
 int linear_run(const void* a, const void* w, int M, int N, int K, int epilogue, const void* residual, void* out,
-               int out_chunk, int tm_override, hipStream_t st);
+               int out_chunk, int tm_override, hipStream_t st, const float2* rope_cs = nullptr, int rope_dh = 0);
+int rope_table_run(const int32_t* pos, int rows, int dh, float theta, float2* table, hipStream_t st);
 int rmsnorm_run(const void* x, const void* gain, int rows, int d, float eps, void* y, hipStream_t st);
 int rope_run(void* q, void* k, const int32_t* pos, int rows, int H, int dh, float theta, hipStream_t st);
 int linear_split_plan(int M, int N, int K);
@@ -69,7 +70,7 @@ __global__ void stack_copy_i32_kernel(const int32_t* __restrict__ src, int32_t* 
 }
 
 struct StackWs {
-    size_t meta, pos, h, hm, nrm, qkv, att, act, part, scores, kept, slot, assign, sub, sub_bytes, total;
+    size_t meta, pos, rope, h, hm, nrm, qkv, att, act, part, scores, kept, slot, assign, sub, sub_bytes, total;
 };
 // sum_N / max_N: total and largest token count; sum_V / max_V likewise for the visual blocks
 StackWs stack_ws_layout(int B, int sum_N, int max_N, int d, int H, int F, int sum_V, int max_V, int max_D) {
@@ -80,6 +81,7 @@ StackWs stack_ws_layout(int B, int sum_N, int max_N, int d, int H, int F, int su
     const size_t vis = (size_t)(sum_V > 0 ? sum_V : 1) * 4;
     w.meta = take(META_INTS * 4);
     w.pos = take((size_t)sum_N * 4);
+    w.rope = take((size_t)sum_N * (d / H / 2) * sizeof(float2));      // (cos, sin) of every token's rotary angles
     w.h = take(act_row); w.hm = take(act_row); w.nrm = take(act_row);
     w.qkv = take(3 * act_row);             // q, k, v of the current length, back to back
     w.att = take(act_row);
@@ -167,6 +169,7 @@ extern "C" int d3tom_stack_step_batch(const void* x, int B, const int32_t* N_h, 
     char* base = (char*)ws;
     int32_t* meta = (int32_t*)(base + w.meta);
     int32_t* pos = (int32_t*)(base + w.pos);
+    float2* rope_cs = (float2*)(base + w.rope);
     void *h = base + w.h, *hm = base + w.hm, *nrm = base + w.nrm, *qkv = base + w.qkv;
     void *att = base + w.att, *act = base + w.act;
     float* part = (float*)(base + w.part);
@@ -181,6 +184,10 @@ extern "C" int d3tom_stack_step_batch(const void* x, int B, const int32_t* N_h, 
     auto M = [&](int slot_id) { return meta + slot_id * META_STRIDE; };
 
     D3TOM_LAUNCH(STACK_META, st, (stack_meta_kernel<<<ceil_div(sum_N, 256), 256, 0, st>>>(meta, pos, sz, sum_N)));
+    {   // rotary angles of the tokens at their positions; renewed after the merge, when the positions change
+        const int rc = rope_table_run(pos, sum_N, dh, theta, rope_cs, st);
+        if (rc != D3TOM_OK) return rc;
+    }
 
     const void* cur = x;          // hidden state entering the block (the input itself is never written)
     int n = sum_N;                // its row count
@@ -201,8 +208,8 @@ extern "C" int d3tom_stack_step_batch(const void* x, int B, const int32_t* N_h, 
         void* qq = qkv;
         void* kk = (char*)qkv + (size_t)n * d * 2;
         void* vv = (char*)qkv + (size_t)2 * n * d * 2;
-        D3TOM_TRY(linear_run(nrm, b.w_qkv, n, 3 * d, d, LIN_PLAIN, nullptr, qkv, d, 0, st));
-        D3TOM_TRY(rope_run(qq, kk, pos, n, H, dh, theta, st));
+        // the rotation of q and k happens in the projection's epilogue
+        D3TOM_TRY(linear_run(nrm, b.w_qkv, n, 3 * d, d, LIN_PLAIN, nullptr, qkv, d, 0, st, rope_cs, dh));
         D3TOM_TRY(d3tom_attend(qq, kk, vv, D3TOM_BF16, B, cu, longest, H, dh, scale, att, sub, w.sub_bytes, st));
         // post-attention hidden state = residual + attention output projection; in place, except that the
         // caller's input is never written
@@ -230,6 +237,7 @@ extern "C" int d3tom_stack_step_batch(const void* x, int B, const int32_t* N_h, 
                                   st));
             // from here on every stage sees the shortened sequences; pos holds the original positions
             ht = merged;
+            D3TOM_TRY(rope_table_run(pos, sum_out, dh, theta, rope_cs, st));
             n = sum_out;
             longest = max_out;
             cu = M(META_OUT_OFF);

@@ -268,6 +268,7 @@ STACK_CASES = [
     (3, 256, 2, 320, 7, 300, 21, 5, 299, 3),           # merge in the last block, one token merged away
     (2, 256, 4, 512, 0, 200, 8, 8, 1, 1),              # no prompt, everything merged into one token
     (2, 2048, 16, 2048, 10, 120, 20, 6, 30, 1),        # wide enough that the output / down projections are split along k
+    (2, 192, 3, 320, 5, 90, 11, 4, 30, 1),             # three heads of 64: a 128-column projection tile straddles q | k and k | v
 ]
 
 
