@@ -75,31 +75,48 @@ def build_steps(wl_name: str):
 
 
 class Runner:
-    """Shared output buffers + workspaces, and the four launches of one step."""
+    """Shared output buffers + workspaces, and the launches of one step: the merge layer in one call
+    (d3tom_merge_layer, kept counts computed on the device from the keep ratios) followed by the attention;
+    with one_call=False the four separate entry points instead."""
 
-    def __init__(self, wl, dev):
+    def __init__(self, wl, dev, one_call=True):
         from paper_2511_12280_amd import binding as B
-        self.B, self.wl, self.dev = B, wl, dev
+        self.B, self.wl, self.dev, self.one_call = B, wl, dev, one_call
         mx = lambda f: max(f(d["lay"]) for d in dev)
         tdt = torch.float32 if wl.dtype == "f32" else torch.bfloat16
-        self.scores = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.float32, device="cuda")
-        self.kept = torch.zeros(mx(lambda l: l.sum_keep), dtype=torch.int32, device="cuda")
-        self.slot = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.int32, device="cuda")
-        self.y = torch.zeros((mx(lambda l: l.sum_Nm), wl.d), dtype=tdt, device="cuda")
-        self.counts = torch.zeros(mx(lambda l: l.sum_keep), dtype=torch.int32, device="cuda")
-        self.src = torch.zeros(mx(lambda l: l.sum_Nm), dtype=torch.int32, device="cuda")
-        self.o = torch.zeros((mx(lambda l: l.sum_Nm), wl.H, wl.dh), dtype=tdt, device="cuda")
+        i32 = lambda m: torch.zeros(m, dtype=torch.int32, device="cuda")
         nb, mN, mV, mD = mx(lambda l: l.B), mx(lambda l: l.max_N), mx(lambda l: l.max_V), mx(lambda l: l.max_D)
+        self.scores = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.float32, device="cuda")
+        self.kept = i32(nb * mV)
+        self.slot = i32(mx(lambda l: l.sum_V))
+        self.y = torch.zeros((mx(lambda l: l.sum_N), wl.d), dtype=tdt, device="cuda")
+        self.counts = i32(nb * mV)
+        self.src = i32(mx(lambda l: l.sum_N))
+        self.o = torch.zeros((mx(lambda l: l.sum_Nm), wl.H, wl.dh), dtype=tdt, device="cuda")
         self.ws_imp = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_IMPORTANCE, nb, mN, mV, wl.H, wl.dh, mD))
         self.ws_merge = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_MERGE, nb, mN, mV, wl.H, wl.dh, mD))
         self.scale = 1.0 / float(np.sqrt(wl.dh))
+        # the one-call path: keep ratios on the device, the kept counts and offsets are outputs
+        self.keep_k, self.kept_off, self.out_off = i32(nb), i32(nb + 1), i32(nb + 1)
+        self.ws_layer = B.workspace(B.d3tom_merge_layer_workspace_bytes(nb, mN, mV, wl.H, wl.dh, mD))
+        self.ratios = []
+        for d in dev:
+            h = d["host"]
+            r = [h["sch"]["keep_ratio"]] if wl.B == 1 else [k / s["V"] for k, s in zip(h["keeps"], h["samples"])]
+            self.ratios.append(torch.tensor(r, dtype=torch.float64, device="cuda"))
 
     def step(self, i: int):
         B, d = self.B, self.dev[i]
         lay = d["lay"]
-        B.d3tom_importance(d["q"], d["k"], lay, self.scale, self.scores, self.ws_imp)
-        B.d3tom_select_topk(self.scores, lay, self.kept, self.slot)
-        B.d3tom_merge(d["x"], None, lay, self.kept, B.D3TOM_MERGE_MEAN, self.y, None, self.counts, self.src, self.ws_merge)
+        if self.one_call:
+            # tight host bounds on the kept counts: the launch shapes are those of the separate calls
+            B.d3tom_merge_layer(d["q"], d["k"], d["x"], None, lay, self.scale, self.ratios[i], min(lay.keep), max(lay.keep),
+                                B.D3TOM_MERGE_MEAN, self.scores, self.keep_k, self.kept_off, self.kept, self.out_off,
+                                self.y, None, self.counts, self.src, self.ws_layer)
+        else:
+            B.d3tom_importance(d["q"], d["k"], lay, self.scale, self.scores, self.ws_imp)
+            B.d3tom_select_topk(self.scores, lay, self.kept, self.slot)
+            B.d3tom_merge(d["x"], None, lay, self.kept, B.D3TOM_MERGE_MEAN, self.y, None, self.counts, self.src, self.ws_merge)
         B.d3tom_attend(d["qa"], d["ka"], d["va"], d["cu"], lay.max_Nm, self.scale, self.o)
 
 
@@ -132,12 +149,12 @@ def step_order(n: int, K: int):
     return order
 
 
-def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
+def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool, one_call: bool = True):
     from paper_2511_12280_amd import binding as B
     t0 = time.time()
     wl, dev = build_steps(wl_name)
     gen_s = time.time() - t0
-    r = Runner(wl, dev)
+    r = Runner(wl, dev, one_call)
     n = len(dev)
     order = step_order(n, steps)
     for i in range(n):                   # untimed: every step once (first-use set-up, inputs touched)
@@ -194,39 +211,21 @@ def run_workload(wl_name: str, steps: int, warmup: int, cpu_baseline: bool):
     return wl, res
 
 
-def run_merge_layer_one_call(wl_name: str, steps: int, warmup: int):
-    """d3tom_merge_layer over the workload: the merge layer in one call with the kept counts computed on the
-    device from the keep ratios (tight host bounds on them, so the launch shapes are those of the separate calls)."""
-    from paper_2511_12280_amd import binding as B
+def run_separate_calls(wl_name: str, steps: int, warmup: int):
+    """The same steps through the four separate entry points (importance, selection, merge, attention) with the
+    kept counts on the host: what a caller pays who needs a host decision between the stages."""
     wl, dev = build_steps(wl_name)
+    r = Runner(wl, dev, one_call=False)
     n = len(dev)
-    mx = lambda f: max(f(d["lay"]) for d in dev)
-    nb, mN, mV, mD = mx(lambda l: l.B), mx(lambda l: l.max_N), mx(lambda l: l.max_V), mx(lambda l: l.max_D)
-    i32 = lambda m: torch.zeros(m, dtype=torch.int32, device="cuda")
-    scores = torch.zeros(mx(lambda l: l.sum_V), dtype=torch.float32, device="cuda")
-    keep_k, kept_off, out_off, kept_idx = i32(nb), i32(nb + 1), i32(nb + 1), i32(nb * mV)
-    y = torch.zeros((mx(lambda l: l.sum_N), wl.d), dtype=torch.bfloat16 if wl.dtype == "bf16" else torch.float32, device="cuda")
-    counts, src = i32(nb * mV), i32(mx(lambda l: l.sum_N))
-    ws = B.workspace(B.d3tom_merge_layer_workspace_bytes(nb, mN, mV, wl.H, wl.dh, mD))
-    ratios = []
-    for d in dev:
-        h = d["host"]
-        r = [h["sch"]["keep_ratio"]] if wl.B == 1 else [k / s["V"] for k, s in zip(h["keeps"], h["samples"])]
-        ratios.append(torch.tensor(r, dtype=torch.float64, device="cuda"))
-    scale = 1.0 / float(np.sqrt(wl.dh))
-    def step(i):
-        d = dev[i]; lay = d["lay"]
-        B.d3tom_merge_layer(d["q"], d["k"], d["x"], None, lay, scale, ratios[i], min(lay.keep), max(lay.keep),
-                            B.D3TOM_MERGE_MEAN, scores, keep_k, kept_off, kept_idx, out_off, y, None, counts, src, ws)
-    order = step_order(n, steps)
     for i in list(range(n)) + step_order(n, warmup):
-        step(i)
+        r.step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in order:
-        step(i)
+    for i in step_order(n, steps):
+        r.step(i)
     torch.cuda.synchronize()
-    return dict(merge_layer_us=round((time.perf_counter() - t0) * 1e6 / steps, 2), kept_counts="on the device, from the keep ratios")
+    el = time.perf_counter() - t0
+    return dict(steps_per_s=round(steps / el, 2), ms_per_step=round(el * 1e3 / steps, 4))
 
 
 def run_kv_cache(wl_name: str, steps: int, warmup: int):
@@ -486,6 +485,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": f"{wl.name}: {wl.V} visual + {wl.P} prompt + {wl.O} response tokens, hidden {wl.d}, "
                                f"{wl.H}x{wl.dh} heads, batch {wl.B}, {wl.note}", "timed": "inputs resident in HBM",
+                   "calls_per_step": "d3tom_merge_layer (keep ratios on the device) + d3tom_attend",
                    "timed_steps": res["timed_steps"]},
         "merge_layer_us": res["merge_layer_us"], "attend_us": res["attend_us"],
         "roofline": {"kernel": res["dominant"], "bound": dom["bound"], "achieved": dom["achieved"], "peak": dom["peak"],
@@ -515,7 +515,7 @@ def main():
                                                      for n in (231, 263)}
     if also:
         line["also"]["kv_cache_of_" + args.workload] = run_kv_cache(args.workload, args.steps, args.warmup)
-        line["also"]["merge_layer_one_call_" + args.workload] = run_merge_layer_one_call(args.workload, args.steps, args.warmup)
+        line["also"]["separate_calls_" + args.workload] = run_separate_calls(args.workload, args.steps, args.warmup)
         if not args.no_stack:
             line["also"]["denoise_stack_3645"] = run_stack()
     print(json.dumps(line))

@@ -156,7 +156,7 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
-    table_t* __restrict__ table, int VP, int per, int RB, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch) {
+    table_t* __restrict__ table, int VP, int per, int RB, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch, int skew) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BM = TM * 64;
     constexpr int COS_NS = cos_ring_stages(TM);
@@ -223,7 +223,9 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     const uint32_t a_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (BM / 4) * 128);
     const uint32_t b_lds = __builtin_amdgcn_readfirstlane(ring0 + BM * 128 + wave * (COS_BN / 4) * 128);
     // loads [n0, n1) of a stage's LPS loads (A tile first, then B tile)
-    auto issue_part = [&](int kt, int stage, int n0, int n1) {
+    const int koff = (skew * (ct + 7 * rt)) % nkt;
+    auto issue_part = [&](int kt_in, int stage, int n0, int n1) {
+        const int kt = (kt_in + koff >= nkt) ? kt_in + koff - nkt : kt_in + koff;
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
             if (i >= n0 && i < n1)
@@ -732,18 +734,19 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         const dim3 g((unsigned)(8 * per * B), (unsigned)ksplit);
         float* dots = (float*)(wsb + w.dots_off);
         const size_t lds = (size_t)cos_ring_stages(TM) * (BM + COS_BN) * 128;
+        static const int skew = getenv("D3TOM_COS_SKEW") ? atoi(getenv("D3TOM_COS_SKEW")) : 0;
         if (TM == 4)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<4><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct));
+                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct, skew));
         else if (TM == 1)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP, per, RB, ksplit, dots, nrt, nct));
+                rnorm, table, w.VP, per, RB, ksplit, dots, nrt, nct, skew));
         else
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct));
+                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct, skew));
         if (ksplit > 1) {
             const dim3 gr(ceil_div(max_pruned, 4), B);
             D3TOM_LAUNCH(COS_REDUCE, st, cos_reduce_argmax<<<gr, 256, 0, st>>>(

@@ -73,6 +73,27 @@ class GpuStep:
         return dict(y=self.split(B.to_host(self.y), lay.Nm), assign=self.split(B.to_host(self.assign), lay.V),
                     counts=self.split(B.to_host(self.counts), lay.keep), src_pos=self.split(B.to_host(self.src_pos), lay.Nm))
 
+    def merge_layer(self, ratios: Sequence[float]):
+        """The merge layer in one call (d3tom_merge_layer) at tight host bounds on the kept counts, into buffers of
+        its own: (scores, kept, outputs of the merge) in the shape the separate calls return them."""
+        lay = self.lay
+        nb = lay.B
+        i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
+        scores = torch.zeros(lay.sum_V, dtype=torch.float32, device="cuda")
+        keep_k, kept_off, out_off, kept_idx = i32(nb), i32(nb + 1), i32(nb + 1), i32(nb * lay.max_V)
+        y = torch.zeros((lay.sum_N, self.d), dtype=self.y.dtype, device="cuda")
+        assign, counts, src_pos = i32(lay.sum_V), i32(nb * lay.max_V), i32(lay.sum_N)
+        ws = B.workspace(B.d3tom_merge_layer_workspace_bytes(nb, lay.max_N, lay.max_V, self.H, self.dh, lay.max_D))
+        B.d3tom_merge_layer(self.q, self.k, self.x, None, lay, self.scale, torch.tensor(list(ratios), dtype=torch.float64, device="cuda"),
+                            min(lay.keep), max(lay.keep), self.mode, scores, keep_k, kept_off, kept_idx, out_off, y, assign,
+                            counts, src_pos, ws)
+        torch.cuda.synchronize()
+        assert keep_k.cpu().tolist() == lay.keep
+        return (self.split(B.to_host(scores), lay.V), self.split(B.to_host(kept_idx[:lay.sum_keep]), lay.keep),
+                dict(y=self.split(B.to_host(y[:lay.sum_Nm]), lay.Nm), assign=self.split(B.to_host(assign), lay.V),
+                     counts=self.split(B.to_host(counts[:lay.sum_keep]), lay.keep),
+                     src_pos=self.split(B.to_host(src_pos[:lay.sum_Nm]), lay.Nm)))
+
     def merge_kv(self, v_cache_rows: np.ndarray, kept: Optional[List[np.ndarray]] = None):
         """KV-cache variant: the samples' `x` rows play the key cache, `v_cache_rows` [sum N, d] the value cache."""
         if kept is not None:

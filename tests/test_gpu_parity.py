@@ -362,6 +362,13 @@ def test_lavida_3645_sweep_steps_sampled(s_idx):
     st = check_full_sample(step, 0, S, kept, slot, mout, assign_rows=rows)
     n_m = wl.N - (wl.V - k)
     assert mout["y"][0].shape[0] == n_m
+    # the benchmark's step calls the merge layer in one piece, with the keep ratio on the device: same kernels,
+    # same launch shapes, so every output is that of the separate calls bit for bit
+    S1, kept1, m1 = step.merge_layer([sch["keep_ratio"]])
+    np.testing.assert_array_equal(S1[0], S[0])
+    np.testing.assert_array_equal(kept1[0], kept[0])
+    for key in m1:
+        np.testing.assert_array_equal(m1[key][0], mout[key][0])
     qkv = g.attention_inputs(n_m, sch["D"])
     o = gpu_attend([qkv], "bf16")[0]
     check_attend(o, *qkv, "bf16", rows=rng.choice(n_m, size=48, replace=False))
