@@ -43,20 +43,13 @@ __host__ inline MergeWs merge_ws_layout(int B, int max_V) {
     return w;
 }
 size_t merge_ws_bytes(int B, int max_V) { return merge_ws_layout(B, max_V).total; }
-
-// Table entry of a visual token: (order-preserving integer image of its best value so far) << 32 | (2^32-1 - slot).
-// Unsigned comparison of entries = (value, then lower slot); 0 = nothing yet (below every real entry); a kept
-// token holds the largest high word with its own slot and is never a target of an update.
-typedef unsigned long long table_t;
-__device__ __forceinline__ uint32_t value_key(float f) {       // ascending uint order == ascending float order
-    const uint32_t u = __float_as_uint(f);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ table_t table_entry(float value, int slot) {
-    return ((table_t)value_key(value) << 32) | (table_t)(0xFFFFFFFFu - (uint32_t)slot);
-}
-__device__ __forceinline__ table_t table_entry_kept(int slot) {
-    return ((table_t)0xFFFFFFFFu << 32) | (table_t)(0xFFFFFFFFu - (uint32_t)slot);
+void merge_prep_targets(void* merge_ws, int B, int max_V, MergePrep* prep) {
+    const MergeWs w = merge_ws_layout(B, max_V);
+    char* wsb = (char*)merge_ws;
+    prep->pruned = (int32_t*)(wsb + w.pruned_off);
+    prep->rnorm = (float*)(wsb + w.rnorm_off);
+    prep->table = (table_t*)(wsb + w.table_off);
+    prep->VP = w.VP;
 }
 
 struct SampleGeom { int tok0, N, vs, V, k, M; };
@@ -102,32 +95,8 @@ __global__ __launch_bounds__(256) void merge_norms_kernel(
             for (int t = j + 1 + lane; t < s.V; t += 64) { tab[t] = 0; if (t >= s.k) pr[t - s.k] = t; }
         if (lane == 0) tab[j] = table_entry_kept(r);
     }
-    const T* row = f + (size_t)(s.tok0 + s.vs + j) * d;
-    constexpr int EPC = 16 / sizeof(T);       // elements per 16-byte chunk
-    float ss = 0.f;
-    const int nch = d / EPC;
-    for (int c0 = 0; c0 < nch; c0 += 64 * 8) {             // 8 independent 16-byte loads per lane in flight
-        uint4 w8[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int c = c0 + u * 64 + lane;
-            w8[u] = (c < nch) ? *reinterpret_cast<const uint4*>(row + (size_t)c * EPC) : make_uint4(0, 0, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const uint4 w = w8[u];
-            if constexpr (sizeof(T) == 2) {
-                const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { const float a = bf16_lo(ww[e]), c2 = bf16_hi(ww[e]); ss += a * a; ss += c2 * c2; }
-            } else {
-                const float a0 = __uint_as_float(w.x), a1 = __uint_as_float(w.y), a2 = __uint_as_float(w.z), a3 = __uint_as_float(w.w);
-                ss += a0 * a0; ss += a1 * a1; ss += a2 * a2; ss += a3 * a3;
-            }
-        }
-    }
-    ss = wave_sum(ss);
-    if (lane == 0) rnorm[(size_t)b * max_V + r] = 1.0f / fmaxf(sqrtf(ss), 1e-15f);
+    const float ss = row_sum_squares(f + (size_t)(s.tok0 + s.vs + j) * d, d, lane);
+    if (lane == 0) rnorm[(size_t)b * max_V + r] = reciprocal_norm(ss);
 }
 
 // ---- cosine GEMM + fused argmax, bf16 MFMA ---------------------------------------------------
@@ -156,7 +125,7 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     const uint16_t* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
-    table_t* __restrict__ table, int VP, int per, int RB, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch, int skew) {
+    table_t* __restrict__ table, int VP, int per, int RB, int ksplit, float* __restrict__ dots, int nrt_launch, int nct_launch, int rn_by_token) {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BM = TM * 64;
     constexpr int COS_NS = cos_ring_stages(TM);
@@ -212,7 +181,8 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     }
     for (int t = tid; t < COS_BN; t += 512) {
         const int r = ct * COS_BN + t;
-        rnB[t] = (r < s.k) ? rn[r] : 0.f;
+        // 1 / norm of the kept row in slot r: stored by slot, or by token when the selection launch computed them
+        rnB[t] = (r < s.k) ? rn[rn_by_token ? min(max(kp[r], 0), s.V - 1) : r] : 0.f;
     }
     // split-K: slice blockIdx.y of the contraction (ksplit slices of nkt stages each)
     const int nkt = (d / COS_BK) / ksplit;
@@ -223,9 +193,7 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     const uint32_t a_lds = __builtin_amdgcn_readfirstlane(ring0 + wave * (BM / 4) * 128);
     const uint32_t b_lds = __builtin_amdgcn_readfirstlane(ring0 + BM * 128 + wave * (COS_BN / 4) * 128);
     // loads [n0, n1) of a stage's LPS loads (A tile first, then B tile)
-    const int koff = (skew * (ct + 7 * rt)) % nkt;
-    auto issue_part = [&](int kt_in, int stage, int n0, int n1) {
-        const int kt = (kt_in + koff >= nkt) ? kt_in + koff - nkt : kt_in + koff;
+    auto issue_part = [&](int kt, int stage, int n0, int n1) {
 #pragma unroll
         for (int i = 0; i < A_LD; ++i)
             if (i >= n0 && i < n1)
@@ -376,7 +344,7 @@ __global__ __launch_bounds__(256) void cos_reduce_argmax(
     const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
     const float* __restrict__ dots, int ksplit, int n_tiles, int nrt_launch, int nct_launch,
-    table_t* __restrict__ table, int VP) {
+    table_t* __restrict__ table, int VP, const int32_t* __restrict__ kept_idx /* != nullptr: rnorm is indexed by token */) {
     constexpr int BM = 64;
     const int b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
@@ -406,7 +374,7 @@ __global__ __launch_bounds__(256) void cos_reduce_argmax(
                 float sum = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < 16; ++ks) sum += v[half][ks];        // ascending slices; absent ones add 0
-                const float val = sum * rn[slot];
+                const float val = sum * rn[kept_idx ? min(max(kept_idx[kept_off[b] + slot], 0), s.V - 1) : slot];
                 if (val > best) { best = val; bidx = slot; }
             }
         }
@@ -431,7 +399,7 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
     const T* __restrict__ f, int d, const int32_t* __restrict__ seq_off, const int32_t* __restrict__ vis_start,
     const int32_t* __restrict__ vis_count, const int32_t* __restrict__ kept_idx, const int32_t* __restrict__ kept_off,
     int max_V, int max_keep, const int32_t* __restrict__ pruned, const float* __restrict__ rnorm,
-    table_t* __restrict__ table, int VP) {
+    table_t* __restrict__ table, int VP, int rn_by_token) {
     const int p = blockIdx.x, b = blockIdx.y;
     const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
     if (p >= s.M) return;
@@ -448,7 +416,7 @@ __global__ __launch_bounds__(256) void cos_argmax_generic(
         float dot = 0.f;
         for (int cidx = lane; cidx < d; cidx += 64) dot += Elem<T>::load(xm + cidx) * Elem<T>::load(xk + cidx);
         dot = wave_sum(dot);
-        const float v = dot * rn[r];        // the pruned row's own norm scales all its candidates alike
+        const float v = dot * rn[rn_by_token ? j : r];        // the pruned row's own norm scales all its candidates alike
         if (v > bv) { bv = v; bi = r; }
     }
     if (lane == 0) red[wave] = make_float2(bv, __int_as_float(bi));
@@ -665,7 +633,7 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
                      const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
                      int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
                      const int32_t* out_off, int32_t* assign, int32_t* counts, int32_t* src_pos,
-                     void* ws, size_t ws_bytes, void* stream) {
+                     void* ws, size_t ws_bytes, void* stream, bool prepared) {
     if (!x0 || !y0 || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off)
         return D3TOM_ERR_INVALID_ARG;
     if ((x1 == nullptr) != (y1 == nullptr)) return D3TOM_ERR_INVALID_ARG;
@@ -697,8 +665,11 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         }))
         return D3TOM_ERR_DEVICE;
 
+    // prepared: the selection launch has left 1 / norm of every visual row (by token), the pruned list and the
+    // initial table in the workspace
     const dim3 gn(ceil_div(max_keep, 4), B);
-    if (dt == D3TOM_BF16)
+    if (prepared) {
+    } else if (dt == D3TOM_BF16)
         D3TOM_LAUNCH(MERGE_NORMS, st, merge_norms_kernel<uint16_t><<<gn, 256, 0, st>>>(
             (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, rnorm, pruned,
             table, w.VP));
@@ -734,35 +705,35 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
         const dim3 g((unsigned)(8 * per * B), (unsigned)ksplit);
         float* dots = (float*)(wsb + w.dots_off);
         const size_t lds = (size_t)cos_ring_stages(TM) * (BM + COS_BN) * 128;
-        static const int skew = getenv("D3TOM_COS_SKEW") ? atoi(getenv("D3TOM_COS_SKEW")) : 0;
+        const int by_token = prepared ? 1 : 0;
         if (TM == 4)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<4><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct, skew));
+                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct, by_token));
         else if (TM == 1)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<1><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP, per, RB, ksplit, dots, nrt, nct, skew));
+                rnorm, table, w.VP, per, RB, ksplit, dots, nrt, nct, by_token));
         else
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_bf16<2><<<g, 512, lds, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct, skew));
+                rnorm, table, w.VP, per, RB, 1, dots, nrt, nct, by_token));
         if (ksplit > 1) {
             const dim3 gr(ceil_div(max_pruned, 4), B);
             D3TOM_LAUNCH(COS_REDUCE, st, cos_reduce_argmax<<<gr, 256, 0, st>>>(
                 seq_off, vis_start, vis_count, kept_off, max_V, max_keep, pruned, rnorm, dots, ksplit,
-                nrt * nct * B, nrt, nct, table, w.VP));
+                nrt * nct * B, nrt, nct, table, w.VP, prepared ? kept_idx : nullptr));
         }
     } else if (max_pruned > 0) {
         const dim3 g(max_pruned, B);
         if (dt == D3TOM_BF16)
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_generic<uint16_t><<<g, 256, 0, st>>>(
                 (const uint16_t*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP));
+                rnorm, table, w.VP, prepared ? 1 : 0));
         else
             D3TOM_LAUNCH(COS_ARGMAX, st, cos_argmax_generic<float><<<g, 256, 0, st>>>(
                 (const float*)sim, d_sim, seq_off, vis_start, vis_count, kept_idx, kept_off, max_V, max_keep, pruned,
-                rnorm, table, w.VP));
+                rnorm, table, w.VP, prepared ? 1 : 0));
     }
 
     // few output rows (short sequences): two workgroups per row, half a row each, so that more CUs stream

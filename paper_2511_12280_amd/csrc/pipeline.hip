@@ -48,17 +48,24 @@ extern "C" int d3tom_merge_layer(const void* q, const void* k, const void* x, co
     rc = importance_run(q, k, dt, B, seq_off, H, dh, scale, dec_idx, dec_off, max_D, vis_start, vis_count, vis_off, max_N,
                         max_V, scores, base + w.imp, stream);
     if (rc != D3TOM_OK) return rc;
-    // while the selection runs on one compute unit per sample, the others stream the rows the cosine kernel gathers next
-    RowPrefetch pf;
-    pf.base = sim ? sim : x;
-    pf.row_bytes = (sim ? d_sim : d) * (dt == D3TOM_BF16 ? 2 : 4);
-    pf.vis_start = vis_start;
-    pf.vis_count = vis_count;
+    // The selection leaves most of the chip idle: its launch carries workgroups that stream the visual rows of the
+    // similarity features and leave their norms, so that the rows are in the memory-side cache when the cosine kernel
+    // gathers them and the merge needs no norms launch; the selecting workgroup writes the pruned list and the token
+    // table.  (Giving half of the rows to the second importance launch was measured and lost: that kernel slows down
+    // by more than the selection gains.)
+    MergePrep prep;
+    prep.feat = sim ? sim : x;
+    prep.d = sim ? d_sim : d;
+    prep.dt = dt;
+    prep.vis_start = vis_start;
+    prep.vis_count = vis_count;
+    merge_prep_targets(base + w.merge, B, max_V, &prep);
+    bool prepared = false;
     rc = topk_run(scores, B, vis_off, nullptr, nullptr, max_V, kept_idx, (int32_t*)(base + w.slot), keep_ratio, seq_off, keep_k,
-                  kept_off, out_off, stream, pf);
+                  kept_off, out_off, stream, &prep, &prepared);
     if (rc != D3TOM_OK) return rc;
     // launch sizes from the host-known bounds on the kept counts; workgroups beyond a sample's real sizes exit at once
     return merge_run(x, y, nullptr, nullptr, sim, d, d_sim, dt, B, seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off,
                      max_N, max_V, max_keep, max_V - min_keep, max_N, mode, out_off, assign, counts, src_pos,
-                     base + w.merge, merge_ws_bytes(B, max_V), stream);
+                     base + w.merge, merge_ws_bytes(B, max_V), stream, prepared);
 }

@@ -11,17 +11,18 @@
 // histograms keep those same-address updates from serialising across the whole workgroup.
 //
 // The selection is a chain of short dependent passes on one compute unit per sample.  Called from the one-call
-// merge layer, the launch carries further workgroups (blockIdx.y > 0) that do not select anything: they read
-// the sample's visual rows of the feature tensor front to back and drop them, which leaves the rows in the
-// memory-side cache for the gathers of the cosine kernel (a sequential read of cold rows is several times
-// cheaper than the 128-byte gathers that kernel would otherwise send to HBM).
+// merge layer, the launch carries further workgroups (blockIdx.y > 0) that do not select anything: one wave per
+// visual row, they read the rows of the similarity features front to back and store 1 / norm of each.  That
+// leaves the rows in the memory-side cache for the gathers of the cosine kernel (a sequential read of cold rows
+// is several times cheaper than the 128-byte gathers that kernel would otherwise send to HBM) and replaces the
+// merge's norms launch; the selecting workgroup writes the pruned list and the initial token table beside the
+// kept list.
 #include "internal.hpp"
 
 namespace d3tom {
 
 constexpr int TOPK_THREADS = 1024;
 constexpr int TOPK_STREAM_WGS = 255;       // streaming workgroups per launch: one per compute unit the selection leaves idle
-constexpr size_t TOPK_STREAM_MIN_BYTES = (size_t)12 << 20, TOPK_STREAM_MAX_BYTES = (size_t)160 << 20;
 
 __device__ __forceinline__ uint32_t order_key(float f) {       // ascending uint order == ascending float order
     const uint32_t u = __float_as_uint(f);
@@ -64,25 +65,12 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
     const float* __restrict__ scores, const int32_t* __restrict__ score_off, const int32_t* __restrict__ keep_k,
     const int32_t* __restrict__ kept_off, int max_V, int32_t* __restrict__ kept_idx, int32_t* __restrict__ slot_of,
     const double* __restrict__ keep_ratio, const int32_t* __restrict__ seq_off, int32_t* __restrict__ keep_k_out,
-    int32_t* __restrict__ kept_off_out, int32_t* __restrict__ out_off_out, RowPrefetch pf) {
+    int32_t* __restrict__ kept_off_out, int32_t* __restrict__ out_off_out, MergePrep prep) {
     extern __shared__ uint32_t ukey[];                 // [max_V]
     if (blockIdx.y > 0) {
-        // streaming workgroups: rows [vis_start, vis_start + V) of sample blockIdx.x, clamped to the sample
-        const int bb = blockIdx.x;
-        const int n = seq_off[bb + 1] - seq_off[bb];
-        const int vs = min(max(pf.vis_start[bb], 0), n);
-        const int cnt = min(max(pf.vis_count[bb], 0), n - vs);
-        const uint4* p = reinterpret_cast<const uint4*>(static_cast<const char*>(pf.base) + (size_t)(seq_off[bb] + vs) * pf.row_bytes);
-        const size_t n16 = (size_t)cnt * (pf.row_bytes >> 4);
-        const size_t stride = (size_t)(gridDim.y - 1) * TOPK_THREADS;
-        uint32_t acc = 0;
-        size_t i = (size_t)(blockIdx.y - 1) * TOPK_THREADS + threadIdx.x;
-        for (; i + 3 * stride < n16; i += 4 * stride) {
-            const uint4 a = p[i], b2 = p[i + stride], c2 = p[i + 2 * stride], d2 = p[i + 3 * stride];
-            acc ^= a.x ^ b2.x ^ c2.x ^ d2.x;
-        }
-        for (; i < n16; i += stride) acc ^= p[i].x;
-        asm volatile("" : : "v"(acc));         // the loads stay, their values go nowhere
+        // streaming workgroups: norms of the sample's visual rows
+        stream_row_norms(prep, max_V, blockIdx.x, seq_off, (int)(blockIdx.y - 1) * (TOPK_THREADS / 64) + (int)(threadIdx.x >> 6),
+                         (int)(gridDim.y - 1) * (TOPK_THREADS / 64), threadIdx.x & 63);
         return;
     }
     __shared__ int whist[16][256];        // one digit histogram per wave: same-bin updates only collide inside a wave
@@ -220,6 +208,11 @@ __global__ __launch_bounds__(TOPK_THREADS) void topk_select_kernel(
         const bool keep = (u > thr) || (u == thr && e < remaining);
         e += (u == thr);
         slot_of[s0 + j] = keep ? slot : -1;
+        if (prep.table) {
+            // slot = kept tokens in front of j: a pruned token sits at position j - slot of the ascending pruned list
+            prep.table[(size_t)b * prep.VP + j] = keep ? table_entry_kept(slot) : (table_t)0;
+            if (!keep) prep.pruned[(size_t)b * max_V + (j - slot)] = j;
+        }
         if (keep) { kept_idx[k0 + slot] = j; ++slot; }
     }
 }
@@ -230,7 +223,9 @@ using namespace d3tom;
 
 int d3tom::topk_run(const float* scores, int B, const int32_t* score_off, const int32_t* keep_k, const int32_t* kept_off,
                     int max_V, int32_t* kept_idx, int32_t* slot_of, const double* keep_ratio, const int32_t* seq_off,
-                    int32_t* keep_k_out, int32_t* kept_off_out, int32_t* out_off_out, void* stream, RowPrefetch pf) {
+                    int32_t* keep_k_out, int32_t* kept_off_out, int32_t* out_off_out, void* stream, const MergePrep* prep_in,
+                    bool* prepared) {
+    if (prepared) *prepared = false;
     if (!scores || !score_off || !kept_idx || !slot_of) return D3TOM_ERR_INVALID_ARG;
     if (keep_ratio ? (!seq_off || !keep_k_out || !kept_off_out || !out_off_out) : (!keep_k || !kept_off)) return D3TOM_ERR_INVALID_ARG;
     if (B < 1 || max_V < 1) return D3TOM_ERR_INVALID_ARG;
@@ -238,17 +233,12 @@ int d3tom::topk_run(const float* scores, int B, const int32_t* score_off, const 
     static PerDeviceOnce lds_setup;
     if (!lds_setup.run([] { return raise_dynamic_lds(topk_select_kernel, D3TOM_MAX_VISUAL * 4); })) return D3TOM_ERR_DEVICE;
     hipStream_t st = (hipStream_t)stream;
-    // streaming workgroups only where their row range can be formed (the per-sample offsets) and read 16 bytes at a time
-    // and where it pays: a few megabytes are not worth the longer launch, and rows that overflow the memory-side
-    // cache (256 MB, shared with everything else the step touches) would be gone again before they are used
-    const size_t stream_bytes = (size_t)B * max_V * (size_t)pf.row_bytes;
-    const bool streaming = pf.base && seq_off && pf.vis_start && pf.vis_count && pf.row_bytes >= 16 && pf.row_bytes % 16 == 0 &&
-                           (((uintptr_t)pf.base) & 15u) == 0 && stream_bytes >= TOPK_STREAM_MIN_BYTES &&
-                           stream_bytes <= TOPK_STREAM_MAX_BYTES;
-    if (!streaming) pf = RowPrefetch();
+    const bool streaming = merge_prep_usable(prep_in, B, max_V, seq_off);
+    const MergePrep prep = streaming ? *prep_in : MergePrep();
     const int extra = streaming ? (B >= TOPK_STREAM_WGS ? 1 : TOPK_STREAM_WGS / B) : 0;
     D3TOM_LAUNCH(TOPK_SELECT, st, topk_select_kernel<<<dim3(B, 1 + extra), TOPK_THREADS, (size_t)max_V * 4, st>>>(
-        scores, score_off, keep_k, kept_off, max_V, kept_idx, slot_of, keep_ratio, seq_off, keep_k_out, kept_off_out, out_off_out, pf));
+        scores, score_off, keep_k, kept_off, max_V, kept_idx, slot_of, keep_ratio, seq_off, keep_k_out, kept_off_out, out_off_out, prep));
+    if (prepared) *prepared = streaming;
     return D3TOM_OK;
 }
 
