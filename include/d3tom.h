@@ -243,6 +243,11 @@ int d3tom_merge_kv(const void* k_cache, const void* v_cache, int d, int dt,
  *   y           [sum of output rows, d] out; room for seq_off[B] rows is always enough
  *   assign, counts, src_pos   optional outputs as in d3tom_merge
  *   all other arguments as in d3tom_importance / d3tom_merge; vis_off = prefix sums of vis_count
+ * Results are those of the three separate calls, bit for bit when the bounds are tight.  The selection launch
+ * also reads every visual row of the similarity features once (it computes the row norms there, on compute
+ * units the selection leaves idle, and the rows are then cached for the cosine step), so vis_start / vis_count
+ * must describe rows inside x (sim) as for d3tom_merge; batches whose visual rows exceed 160 MB take the plain
+ * sequence of launches.
  * Workspace: d3tom_merge_layer_workspace_bytes.  Statuses as for the separate calls (an empty decider set
  * returns D3TOM_ERR_NO_DECIDERS before anything is enqueued).
  * ---------------------------------------------------------------------------------------- */
