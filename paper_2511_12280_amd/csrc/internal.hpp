@@ -120,13 +120,14 @@ int topk_run(const float* scores, int B, const int32_t* score_off, const int32_t
              int32_t* kept_off_out, int32_t* out_off_out, void* stream, const MergePrep* prep = nullptr,
              bool* prepared = nullptr);
 
-// d3tom_merge / d3tom_merge_kv; prepared: the selection launch has filled the workspace as MergePrep describes
+// d3tom_merge / d3tom_merge_kv; prepared: the selection launch has filled the workspace as MergePrep describes;
+// out_rows_hint: output rows per sample to expect when max_out is only a loose bound (tuning only)
 int merge_run(const void* x0, void* y0, const void* x1, void* y1, const void* sim, int d, int d_sim, int dt,
               int B, const int32_t* seq_off, const int32_t* vis_start, const int32_t* vis_count,
               const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
               int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
               const int32_t* out_off, int32_t* assign, int32_t* counts, int32_t* src_pos,
-              void* ws, size_t ws_bytes, void* stream, bool prepared = false);
+              void* ws, size_t ws_bytes, void* stream, bool prepared = false, int out_rows_hint = 0);
 size_t merge_ws_bytes(int B, int max_V);
 
 }  // namespace d3tom

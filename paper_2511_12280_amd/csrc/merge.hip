@@ -633,7 +633,7 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
                      const int32_t* vis_off, const int32_t* kept_idx, const int32_t* kept_off,
                      int max_N, int max_V, int max_keep, int max_pruned, int max_out, int mode,
                      const int32_t* out_off, int32_t* assign, int32_t* counts, int32_t* src_pos,
-                     void* ws, size_t ws_bytes, void* stream, bool prepared) {
+                     void* ws, size_t ws_bytes, void* stream, bool prepared, int out_rows_hint) {
     if (!x0 || !y0 || !seq_off || !vis_start || !vis_count || !vis_off || !kept_idx || !kept_off || !out_off)
         return D3TOM_ERR_INVALID_ARG;
     if ((x1 == nullptr) != (y1 == nullptr)) return D3TOM_ERR_INVALID_ARG;
@@ -738,7 +738,9 @@ int d3tom::merge_run(const void* x0, void* y0, const void* x1, void* y1, const v
 
     // few output rows (short sequences): two workgroups per row, half a row each, so that more CUs stream
     const int nch = d / epc;
-    const int nslice = ((long)max_out * B * (x1 ? 2 : 1) < 768 && nch >= 512) ? 2 : 1;
+    // (max_out bounds the rows and sizes the grid; when it is only a loose bound, the caller's expected row count decides)
+    const int rows_expected = (out_rows_hint > 0 && out_rows_hint < max_out) ? out_rows_hint : max_out;
+    const int nslice = ((long)rows_expected * B * (x1 ? 2 : 1) < 768 && nch >= 512) ? 2 : 1;
     const dim3 gs(max_out * nslice, B, x1 ? 2 : 1);    // output rows (x slices) per sample x payloads; surplus workgroups exit at once
 #define D3TOM_SCATTER(TYPE, CPT)                                                                                        \
     D3TOM_LAUNCH(MERGE_SCATTER, st, merge_scatter_kernel<TYPE, CPT><<<gs, 256, 0, st>>>(                                \

@@ -67,5 +67,5 @@ extern "C" int d3tom_merge_layer(const void* q, const void* k, const void* x, co
     // launch sizes from the host-known bounds on the kept counts; workgroups beyond a sample's real sizes exit at once
     return merge_run(x, y, nullptr, nullptr, sim, d, d_sim, dt, B, seq_off, vis_start, vis_count, vis_off, kept_idx, kept_off,
                      max_N, max_V, max_keep, max_V - min_keep, max_N, mode, out_off, assign, counts, src_pos,
-                     base + w.merge, merge_ws_bytes(B, max_V), stream, prepared);
+                     base + w.merge, merge_ws_bytes(B, max_V), stream, prepared, max_N - max_V + max_keep);
 }
