@@ -273,6 +273,32 @@ def test_merge_layer_one_call_with_device_side_keep_counts(tight):
             check_full_sample(ref, b, S, kept, slot, got)
 
 
+@pytest.mark.parametrize("dtype,d,H,shapes", [
+    ("f32", 96, 2, [(5, 90, 7, 3, 0.3), (0, 33, 4, 2, 0.5), (9, 200, 1, 6, 0.12)]),       # float32: the generic kernels
+    ("bf16", 4096, 32, [(8, 260, 6, 3, 0.15)]),                                           # one short sample: cosine GEMM cut along the contraction
+    ("bf16", 200, 5, [(3, 150, 5, 4, 0.4), (6, 61, 2, 1, 0.7)]),                          # bf16 rows of 400 bytes, head size 40: generic kernels
+])
+def test_merge_layer_one_call_on_every_kernel_path(dtype, d, H, shapes):
+    """The one-call merge layer prepares the merge inside its selection launch (row norms by token, pruned list,
+    token table); every cosine kernel reads that form.  Each path against the separate calls, bit for bit, and
+    the separate calls against the oracle."""
+    samples, ratios = [], []
+    for i, (P, V, O, D, keep) in enumerate(shapes):
+        samples.append(W.random_case(500 + i, P + V + O, d, H, P, V, D, dtype=dtype, centres=max(3, V // 6)))
+        ratios.append(keep)
+    keeps = [oracle.keep_count(s["V"], r) for s, r in zip(samples, ratios)]
+    ref = GpuStep(samples, keeps, dtype)
+    S = ref.importance(); kept, slot = ref.select_topk(); mout = ref.merge()
+    for b in range(len(samples)):
+        check_full_sample(ref, b, S, kept, slot, mout)
+    S1, kept1, m1 = ref.merge_layer(ratios)
+    for b in range(len(samples)):
+        np.testing.assert_array_equal(S1[b], S[b])
+        np.testing.assert_array_equal(kept1[b], kept[b])
+        for key in m1:
+            np.testing.assert_array_equal(m1[key][b], mout[key][b])
+
+
 # ---- degenerate inputs the oracle defines ------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,d,H", [("bf16", 512, 4), ("bf16", 4096, 32), ("f32", 96, 2)])
 def test_zero_rows_in_the_similarity_features(dtype, d, H):
