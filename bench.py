@@ -299,6 +299,49 @@ def time_attention(wl_name: str, n_tokens: int, steps: int, warmup: int) -> floa
     return (time.perf_counter() - t0) * 1e6 / steps
 
 
+def run_cosine_cold_warm(reps: int = 6):
+    """The cosine kernel of d3tom_merge alone at 3645 visual rows of 4096 bf16, over kept counts, in three memory
+    states: the same tensor as the previous call (rows in the memory-side cache), a different tensor every call
+    (rows cold in HBM, as in the sweep), and a different tensor read front to back just before the call.
+    Microseconds per launch from the library's HIP-event brackets; prints a table (the evidence behind the
+    row-streaming workgroups of the one-call merge layer)."""
+    from paper_2511_12280_amd import binding as B
+    V, d, NX = 3645, 4096, 12
+    rng = np.random.default_rng(5)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    xs = [torch.randn((V, d), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(NX)]
+    y = torch.empty((V, d), dtype=torch.bfloat16, device="cuda")
+    counts = torch.empty(V, dtype=torch.int32, device="cuda")
+    src = torch.empty(V, dtype=torch.int32, device="cuda")
+    ws = B.workspace(B.d3tom_workspace_bytes(B.D3TOM_OP_MERGE, 1, V, V, 32, 128, 64))
+    rows = []
+    for k in (365, 512, 647, 694, 741, 768, 788, 882, 1023, 1030, 1280, 1500, 1822):
+        lay = B.Layout([V], [0], [V], [[0]], [k])
+        kept = torch.from_numpy(np.sort(rng.choice(V, k, replace=False)).astype(np.int32)).cuda()
+        res = {}
+        for state in ("same_tensor", "cold", "read_before"):
+            def call(i):
+                x = xs[0] if state == "same_tensor" else xs[i % NX]
+                if state == "read_before":
+                    x.view(torch.int32).sum()
+                B.d3tom_merge(x, None, lay, kept, B.D3TOM_MERGE_MEAN, y, None, counts, src, ws)
+            for i in range(3):
+                call(i)
+            torch.cuda.synchronize()
+            B.d3tom_profile_enable(True)
+            for i in range(reps):
+                call(3 + i)
+            torch.cuda.synchronize()
+            prof = B.d3tom_profile_collect()
+            B.d3tom_profile_enable(False)
+            res[state] = prof["cos_argmax"][0] * 1e3 / prof["cos_argmax"][1]
+        rows.append((k, res))
+    print("cosine kernel of d3tom_merge, 3645 visual rows x 4096 bf16, microseconds per launch (HIP events around the launch)")
+    print(f"{'kept':>6s} {'pruned':>7s} {'same tensor':>12s} {'cold':>8s} {'read before':>12s}")
+    for k, r in rows:
+        print(f"{k:6d} {V - k:7d} {r['same_tensor']:12.1f} {r['cold']:8.1f} {r['read_before']:12.1f}")
+
+
 def run_stack(traj_repeats: int = 1):
     """Whole denoising trajectory through the 32-block stack (the full-stack configuration): T steps, each
     = decider update on the device, embedding of the current response tokens (one row gather, plumbing),
@@ -457,6 +500,8 @@ def main():
     ap.add_argument("--no-stack", action="store_true", help="skip the full 32-block stack trajectory")
     ap.add_argument("--stack-only", action="store_true",
                     help="run only the 32-block stack trajectory and print its record (for profiling that part alone)")
+    ap.add_argument("--cosine-cold-warm", action="store_true",
+                    help="time the cosine kernel alone with its rows cached / cold / read just before, print a table and exit")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy, the known-size reference for HBM counters")
     args = ap.parse_args()
@@ -472,6 +517,9 @@ def main():
         b.copy_(a)
         torch.cuda.synchronize()
         del a, b
+    if args.cosine_cold_warm:
+        run_cosine_cold_warm()
+        return
     if args.stack_only:
         print(json.dumps(run_stack()))
         return
