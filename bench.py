@@ -491,9 +491,15 @@ def measured_traffic(wl_name: str):
                 acc[name] = (b + (fetch + write) * 1e6 * launches, n + launches)
     out = {k: b / n for k, (b, n) in acc.items() if n}
     note = "from profiles/lavida_3645_sweep_hbm_traffic.txt (two rocprofv3 --pmc runs over whole sweeps), not measured in this run"
-    lib = os.path.join(ROOT, "paper_2511_12280_amd", "libd3tom.so")
-    if os.path.exists(lib) and os.path.getmtime(TRAFFIC_PROFILE) < os.path.getmtime(lib):
-        note += "; the summary is older than the library"
+    # the summary names the kernel sources it was measured on (a digest); say whether they are the current ones
+    from paper_2511_12280_amd.build import source_digest
+    m = re.search(r"kernel sources digest: ([0-9a-f]+)", open(TRAFFIC_PROFILE).read())
+    if m is None:
+        note += "; the summary does not say which sources it was measured on"
+    elif m.group(1) != source_digest():
+        note += "; the kernel sources have changed since the summary was taken"
+    else:
+        note += ", on the current kernel sources"
     return out, note
 
 
