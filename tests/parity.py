@@ -73,10 +73,11 @@ class GpuStep:
         return dict(y=self.split(B.to_host(self.y), lay.Nm), assign=self.split(B.to_host(self.assign), lay.V),
                     counts=self.split(B.to_host(self.counts), lay.keep), src_pos=self.split(B.to_host(self.src_pos), lay.Nm))
 
-    def merge_layer(self, ratios: Sequence[float]):
+    def merge_layer(self, ratios: Sequence[float], sim_rows: Optional[np.ndarray] = None):
         """The merge layer in one call (d3tom_merge_layer) at tight host bounds on the kept counts, into buffers of
         its own: (scores, kept, outputs of the merge) in the shape the separate calls return them."""
         lay = self.lay
+        sim = B.to_device(sim_rows, self.dtype) if sim_rows is not None else None
         nb = lay.B
         i32 = lambda n: torch.full((n,), -7, dtype=torch.int32, device="cuda")
         scores = torch.zeros(lay.sum_V, dtype=torch.float32, device="cuda")
@@ -84,7 +85,7 @@ class GpuStep:
         y = torch.zeros((lay.sum_N, self.d), dtype=self.y.dtype, device="cuda")
         assign, counts, src_pos = i32(lay.sum_V), i32(nb * lay.max_V), i32(lay.sum_N)
         ws = B.workspace(B.d3tom_merge_layer_workspace_bytes(nb, lay.max_N, lay.max_V, self.H, self.dh, lay.max_D))
-        B.d3tom_merge_layer(self.q, self.k, self.x, None, lay, self.scale, torch.tensor(list(ratios), dtype=torch.float64, device="cuda"),
+        B.d3tom_merge_layer(self.q, self.k, self.x, sim, lay, self.scale, torch.tensor(list(ratios), dtype=torch.float64, device="cuda"),
                             min(lay.keep), max(lay.keep), self.mode, scores, keep_k, kept_off, kept_idx, out_off, y, assign,
                             counts, src_pos, ws)
         torch.cuda.synchronize()

@@ -299,6 +299,33 @@ def test_merge_layer_one_call_on_every_kernel_path(dtype, d, H, shapes):
             np.testing.assert_array_equal(m1[key][b], mout[key][b])
 
 
+@pytest.mark.parametrize("d_sim", [128, 72])          # MFMA cosine path (a multiple of 64) and the generic one
+def test_merge_layer_one_call_with_separate_similarity_features(d_sim):
+    """`sim` != x in the one-call merge layer: the selection launch takes its row norms from `sim` (other row length
+    than the payload), the payload rows come from x.  Against d3tom_merge with the same `sim`, bit for bit, and that
+    against the oracle's assignment on the `sim` rows."""
+    shapes = [(4, 210, 6, 3, 0.2), (0, 77, 3, 2, 0.6)]
+    samples, ratios = [], []
+    for i, (P, V, O, D, keep) in enumerate(shapes):
+        samples.append(W.random_case(600 + i, P + V + O, 256, 4, P, V, D, dtype="bf16", centres=9))
+        ratios.append(keep)
+    keeps = [oracle.keep_count(s["V"], r) for s, r in zip(samples, ratios)]
+    rng = np.random.default_rng(601)
+    sim_rows = W.round_to(rng.standard_normal((sum(s["N"] for s in samples), d_sim)).astype(np.float32), "bf16")
+    ref = GpuStep(samples, keeps, "bf16")
+    S = ref.importance(); kept, slot = ref.select_topk(); mout = ref.merge(sim_rows=sim_rows)
+    off = 0
+    for b, s in enumerate(samples):
+        check_assign(mout["assign"][b], sim_rows[off:off + s["N"]], s["vis_start"], s["V"], kept[b])
+        off += s["N"]
+    S1, kept1, m1 = ref.merge_layer(ratios, sim_rows=sim_rows)
+    for b in range(len(samples)):
+        np.testing.assert_array_equal(S1[b], S[b])
+        np.testing.assert_array_equal(kept1[b], kept[b])
+        for key in m1:
+            np.testing.assert_array_equal(m1[key][b], mout[key][b])
+
+
 # ---- degenerate inputs the oracle defines ------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,d,H", [("bf16", 512, 4), ("bf16", 4096, 32), ("f32", 96, 2)])
 def test_zero_rows_in_the_similarity_features(dtype, d, H):
