@@ -136,19 +136,30 @@ __global__ __launch_bounds__(512) void cos_argmax_bf16(
     extern __shared__ __attribute__((aligned(16))) char ring[];
     __shared__ float rnB[COS_BN];
 
-    // blockIdx.x = sample * 8 * per + id; id & 7 is the XCD the hardware puts the workgroup on
+    // blockIdx.x = sample * 8 * per + id; id & 7 is the XCD the hardware puts the workgroup on.  The launch is sized
+    // for the largest sample (per = an eighth of its tiles); every sample numbers ITS OWN tiles and cuts that sequence
+    // into 8 equal runs, so that a sample with fewer tiles still loads the 8 XCDs alike (numbered on the launch's
+    // grid, the tiles of a short sample would all fall to the first XCDs).
     const int b = blockIdx.x / (8 * per);
     const int id = blockIdx.x % (8 * per);
-    const int t_lin = (id & 7) * per + (id >> 3);
-    if (t_lin >= nrt_launch * nct_launch) return;
+    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
+    const int nrt_b = min((s.M + BM - 1) / BM, nrt_launch), nct_b = min((s.k + COS_BN - 1) / COS_BN, nct_launch);
+    const int tiles_b = nrt_b * nct_b;
+    const int per_b = (tiles_b + 7) >> 3;
+    if ((id >> 3) >= per_b) return;
+    const int t_lin = (id & 7) * per_b + (id >> 3);
+    if (t_lin >= tiles_b) return;
     int rt, ct;
     {
-        const int band = RB * nct_launch, nfull = nrt_launch / RB;
-        if (t_lin < nfull * band) { const int rem = t_lin % band; rt = (t_lin / band) * RB + rem % RB; ct = rem / RB; }
-        else { const int t2 = t_lin - nfull * band, rl = nrt_launch - nfull * RB; rt = nfull * RB + t2 % rl; ct = t2 / rl; }
+        // bands about as high as a run's block is wide (RB was chosen that way for the launch's grid; a smaller
+        // sample gets its own)
+        int rb = RB;
+        if (per_b < per) { rb = 1; while ((rb + 1) * (rb + 1) <= per_b) ++rb; }
+        rb = min(rb, nrt_b);
+        const int band = rb * nct_b, nfull = nrt_b / rb;
+        if (t_lin < nfull * band) { const int rem = t_lin % band; rt = (t_lin / band) * rb + rem % rb; ct = rem / rb; }
+        else { const int t2 = t_lin - nfull * band, rl = nrt_b - nfull * rb; rt = nfull * rb + t2 % rl; ct = t2 / rl; }
     }
-    const SampleGeom s = sample_geom(b, seq_off, vis_start, vis_count, kept_off, max_V, max_keep);
-    if (rt * BM >= s.M || ct * COS_BN >= s.k) return;
 
     const int tid = threadIdx.x, wave = (tid >> 6) & 3, lane = tid & 63;
     const bool loader = tid >> 8;                          // waves 4..7 only move data, waves 0..3 only compute
