@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void imp_stats_bf16(
     const int32_t* __restrict__ seq_off, const int32_t* __restrict__ dec_idx, const int32_t* __restrict__ dec_off,
     int max_D, int DPAD, int NCH, float2* __restrict__ part, int NKB, float* __restrict__ logits) {
     constexpr int KS = DH / 32;
-    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // heads vary fastest over the grid: workgroups that run together read neighbouring 2*DH-byte pieces of the same key rows
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
     constexpr int KC = IMP_SUB_STATS * 64;
     const int N = min(seq_off[b + 1] - tok0, NCH * KC);               // the workspace holds NCH chunks per head
@@ -177,7 +178,8 @@ __global__ __launch_bounds__(256) void imp_scores_bf16(
     const int32_t* __restrict__ vis_start, const int32_t* __restrict__ vis_count,
     int max_D, int max_V, int DPAD, int NCH, int KC, int VPAD, const float2* __restrict__ part, float* __restrict__ sp) {
     constexpr int KS = DH / 32;
-    const int chunk = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // heads vary fastest over the grid: workgroups that run together read neighbouring 2*DH-byte pieces of the same key rows
+    const int h = blockIdx.x, chunk = blockIdx.y, b = blockIdx.z;
     const int tok0 = seq_off[b];
     const int N = min(seq_off[b + 1] - tok0, NCH * KC);
     const int D = min(dec_off[b + 1] - dec_off[b], max_D);
@@ -468,7 +470,7 @@ int d3tom::importance_run(const void* q, const void* k, int dt,
     if (dt == D3TOM_BF16 && (dh == 128 || dh == 64)) {
         float2* part = (float2*)(wsb + w.part_off);
         float* sp = (float*)(wsb + w.sp_off);
-        const dim3 g1(w.NCH, H, B), g2(w.NCHV, H, B), g3(ceil_div(max_V, 256), B);
+        const dim3 g1(H, w.NCH, B), g2(H, w.NCHV, B), g3(ceil_div(max_V, 256), B);
         const uint16_t* qq = (const uint16_t*)q;
         const uint16_t* kk = (const uint16_t*)k;
         // small decider sets: the first sweep keeps its logits and the scores come from them (K fetched once)
